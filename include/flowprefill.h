@@ -1,0 +1,208 @@
+/*
+ * flowprefill.h -- C ABI of the op-preemptible transformer prefill for AMD MI355X (gfx950).
+ *
+ * The library runs the prefill forward pass of a dense pre-norm decoder (RMSNorm, fused QKV
+ * projection, rotary embedding + paged KV-cache write, causal variable-length GQA attention,
+ * output projection, RMSNorm, fused gate/up projection, SiLU*up, down projection) as a
+ * sequence of individually launched HIP kernels, with a cooperative preemption check at every
+ * operator boundary.  It follows FlowPrefill (arxiv 2602.16603):
+ *   - Section 2.1, Eq. (1)-(2): what a layer computes;
+ *   - Section 5.1 "Operator-Level Preemption": checks between the core operators qkv_proj, attn,
+ *     o_proj, gate_up_proj, down_proj; on a signal the runtime lets the operator in flight
+ *     finish, acknowledges, and suspends the task with its state kept; latency is bounded by
+ *     one operator;
+ *   - Section 4 "Execution Pool": at most one task runs; preempted tasks keep their state until
+ *     resumed; the pool obeys three commands -- submit, preempt, resume.
+ * submit = fp_prefill_begin + fp_prefill_advance, preempt = fp_preempt, resume = fp_resume +
+ * fp_prefill_advance.
+ *
+ * Conventions
+ *   - Every pointer argument says "host" or "device".  Device pointers are plain HIP device
+ *     addresses on the current device.  The library never frees caller memory.
+ *   - All tensors are row-major and token-major.  Weights are [out, in]; y = x W^T.
+ *     w_qkv rows: [Hq*D query rows | Hkv*D key rows | Hkv*D value rows]; w_gate_up rows:
+ *     [F gate rows | F up rows].
+ *   - dtype FP_DTYPE_F32: weights, input hidden states, KV cache and all intermediates are
+ *     fp32 (debug path).  FP_DTYPE_BF16: weights, input hidden states, intermediates and KV
+ *     cache are bf16; accumulation, softmax, norm and SiLU arithmetic is fp32.  In BOTH modes the
+ *     residual stream is kept in fp32 and fp_prefill_hidden returns fp32.
+ *   - Every function returns fp_status; negative values are errors and leave the handle as it
+ *     was.  fp_last_error() gives a thread-local message for the last error on this thread.
+ *   - No C++ exception crosses this boundary.
+ *
+ * One layer is 9 operators (cursor positions 0..8):
+ *   0 rmsnorm_attn  1 qkv_proj  2 rope_kvwrite  3 attn  4 o_proj(+residual)
+ *   5 rmsnorm_mlp   6 gate_up_proj  7 silu_mul  8 down_proj(+residual)
+ * The paper's five boundaries are after positions 1, 3, 4, 6, 8.
+ */
+#ifndef FLOWPREFILL_H
+#define FLOWPREFILL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fp_model fp_model;     /* immutable after create                                  */
+typedef struct fp_prefill fp_prefill; /* one execution task of the Execution Pool (Section 4)    */
+
+typedef enum {
+  FP_OK = 0,          /* advanced; more operators remain                                         */
+  FP_DONE = 1,        /* all n_layers*9 operators finished and the stream is drained             */
+  FP_PREEMPTED = 2,   /* parked at an operator boundary; device quiesced; acknowledgement sent   */
+  FP_ERR_INVALID = -1,
+  FP_ERR_OOM = -2,
+  FP_ERR_STATE = -3,  /* call not legal in the handle's state (e.g. resume of a running task)    */
+  FP_ERR_DEVICE = -4
+} fp_status;
+
+enum { FP_DTYPE_F32 = 0, FP_DTYPE_BF16 = 1 };
+enum { FP_OPS_PER_LAYER = 9 };
+
+/* boundary_mask: bit i set = a preemption check sits after operator i of every layer.          */
+#define FP_BOUNDARY_EVERY_OP 0x1FFu /* all nine operators                                        */
+#define FP_BOUNDARY_PAPER_OPS 0x15Au /* after qkv_proj, attn, o_proj, gate_up_proj, down_proj    */
+#define FP_BOUNDARY_LAYER 0x100u    /* only after down_proj (layer-level preemption, Fig. 5)     */
+#define FP_BOUNDARY_NONE 0x0u       /* none: a preempt request waits for completion (chunk-level)*/
+
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn;
+  float rms_eps, rope_theta;
+  int32_t dtype;            /* FP_DTYPE_*                                                        */
+  int32_t kv_block_tokens;  /* tokens per KV block; must be 16                                   */
+  int64_t kv_num_blocks;    /* size of the block pool; one block id addresses all layers         */
+  int32_t max_position;     /* RoPE table length = largest sequence length (prefix + new tokens) */
+} fp_shape;
+
+/* Device pointers, BORROWED: the caller owns them and keeps them alive and unchanged for the
+ * life of the model.  attn_norm/mlp_norm [hidden]; w_qkv [(Hq+2Hkv)*D, hidden]; w_o [hidden,
+ * Hq*D]; w_gate_up [2*ffn, hidden]; w_down [hidden, ffn]; element type per fp_shape.dtype.
+ * All must be 16-byte aligned.                                                                   */
+typedef struct {
+  const void *attn_norm, *w_qkv, *w_o, *mlp_norm, *w_gate_up, *w_down;
+} fp_layer_weights;
+
+/* Creates a model: validates the shape (hidden, Hq*D, ffn multiples of 8; head_dim 64 or 128 on
+ * the bf16 path; Hq multiple of Hkv), builds the RoPE cos/sin table on the host in fp64 and
+ * uploads it as fp32, and allocates the paged KV pool:
+ *   K pool [n_layers][kv_num_blocks][Hkv][16 tokens][D]   (keys after rotation)
+ *   V pool [n_layers][kv_num_blocks][Hkv][D][16 tokens]   (values, transposed inside a block)
+ * `layers` is a host array of n_layers entries.  `hip_stream` is the hipStream_t every kernel of
+ * this model's tasks is launched on (NULL = the default stream).  Errors: FP_ERR_INVALID,
+ * FP_ERR_OOM, FP_ERR_DEVICE.                                                                      */
+fp_status fp_model_create(const fp_shape* shape, const fp_layer_weights* layers /*host*/,
+                          void* hip_stream, fp_model** out);
+/* Frees the pool, the tables and cached workspaces.  All tasks must have been ended.             */
+void fp_model_destroy(fp_model* model);
+
+/* KV block allocator of the pool (host bookkeeping only).  fp_kv_alloc writes n distinct free
+ * block ids to ids_out (host) or fails with FP_ERR_OOM taking none.  fp_kv_free returns them.    */
+fp_status fp_kv_alloc(fp_model* model, int32_t n, int32_t* ids_out /*host*/);
+fp_status fp_kv_free(fp_model* model, int32_t n, const int32_t* ids /*host*/);
+/* Device base addresses of the K and V pools (layouts above) for inspection by tests.            */
+fp_status fp_model_kv_pools(const fp_model* model, const void** k_pool /*device*/,
+                            const void** v_pool /*device*/);
+
+/* "submit" (Section 4; Alg. 2 submit_new_execution): creates a task for a request set of n_seqs
+ * prompts (or prompt chunks) packed token-major.
+ *   hidden_in    device [T, hidden] in the storage dtype, T = cu_seqlens[n_seqs]; COPIED into
+ *                the benchmark's fp32 residual buffer during this call (caller may reuse it after).
+ *   cu_seqlens   host [n_seqs+1], non-decreasing, cu_seqlens[0] = 0.  Empty sequences allowed.
+ *   cached_lens  host [n_seqs] tokens of each sequence already in the cache (earlier chunks), or
+ *                NULL for all zero.  Token i of sequence s has position cached_lens[s] + i.
+ *   block_tables host [n_seqs, max_blocks] physical block ids covering positions
+ *                0 .. cached_lens[s]+len_s-1 of each sequence (entry b holds positions
+ *                16b..16b+15); NULL = the library allocates blocks from the pool (then
+ *                cached_lens must be NULL/zero) and frees them in fp_prefill_end.
+ *   boundary_mask which operator boundaries carry a preemption check (FP_BOUNDARY_*).
+ * The task starts idle with its cursor at (layer 0, op 0).  Errors: FP_ERR_INVALID (bad
+ * lengths, block id out of range, position beyond max_position), FP_ERR_OOM, FP_ERR_DEVICE.      */
+fp_status fp_prefill_begin(fp_model* model, const void* hidden_in /*device*/,
+                           const int32_t* cu_seqlens /*host*/, int32_t n_seqs,
+                           const int32_t* cached_lens /*host or NULL*/,
+                           const int32_t* block_tables /*host or NULL*/, int32_t max_blocks,
+                           uint32_t boundary_mask, fp_prefill** out);
+
+/* Runs up to max_ops operators from the cursor, one kernel launch sequence per operator, with a
+ * check of the preemption signal at each enabled boundary (Section 5.1).  Returns when the
+ * operators it issued have completed on the device:
+ *   FP_OK         max_ops operators ran, more remain;
+ *   FP_DONE       the last operator of the last layer has completed;
+ *   FP_PREEMPTED  a signal was seen at a boundary: signal cleared, acknowledgement sent, task
+ *                 parked (fp_resume needed before the next advance).
+ * *ops_done (host, may be NULL) receives the number of operators executed by this call.
+ * Only one thread may be inside advance for a given task; fp_preempt may be called from
+ * another thread meanwhile.  FP_ERR_STATE if the task is parked or already done.                 */
+fp_status fp_prefill_advance(fp_prefill* task, int32_t max_ops, int32_t* ops_done /*host*/);
+
+/* How many operators may be enqueued on the stream beyond the one known complete (>= 1).  With
+ * k the host launches operator i only after operator i-k has completed, so a signal is honoured
+ * within k operators.  Default 2 (no launch bubble; at most the running and one queued operator
+ * finish before the acknowledgement).                                                            */
+fp_status fp_prefill_set_launch_ahead(fp_prefill* task, int32_t k);
+
+/* "preempt" (Section 5.1, Fig. 6): thread-safe.  Sets the task's signal and blocks until the
+ * runtime acknowledges at the next enabled boundary with the device quiesced (FP_PREEMPTED), or
+ * until the task completes first (FP_DONE).  On an idle task (no advance in flight) parks it at
+ * once.  FP_ERR_STATE if already parked.  fp_preempt = fp_preempt_signal + fp_preempt_wait; the
+ * split lets a caller time exactly the signal -> acknowledgement interval (Section 6.4).         */
+fp_status fp_preempt(fp_prefill* task);
+fp_status fp_preempt_signal(fp_prefill* task);
+fp_status fp_preempt_wait(fp_prefill* task);
+
+/* "resume" (Alg. 2 resume_execution): parked -> idle; the next advance continues from the
+ * cursor with the task's workspace and KV blocks untouched.  FP_ERR_STATE unless parked.         */
+fp_status fp_resume(fp_prefill* task);
+
+/* Cursor = the next operator to run: layer in [0, n_layers], op in [0, 9).  (n_layers, 0) = done. */
+fp_status fp_prefill_cursor(const fp_prefill* task, int32_t* layer /*host*/, int32_t* op /*host*/);
+
+/* The fp32 residual stream [T, hidden] (device, owned by the task, valid until fp_prefill_end).
+ * After FP_DONE it is the stack's output; at a layer boundary it is that layer's input.          */
+fp_status fp_prefill_hidden(const fp_prefill* task, const void** dev_ptr);
+
+/* The task's block tables (host [n_seqs, max_blocks], owned by the task) and max_blocks.         */
+fp_status fp_prefill_block_tables(const fp_prefill* task, const int32_t** tables_host,
+                                  int32_t* max_blocks /*host*/);
+
+/* Copies positions 0 .. cached_lens[seq]+len_seq-1 of sequence `seq`, layer `layer`, out of the
+ * paged pools into the caller's contiguous device buffers k_out, v_out [len, Hkv, D] (storage
+ * dtype): keys as cached (rotated), values raw.  This is the hand-over format for a decode
+ * instance and what parity tests compare.  Synchronises the stream before returning.             */
+fp_status fp_prefill_kv_gather(const fp_prefill* task, int32_t layer, int32_t seq,
+                               void* k_out /*device*/, void* v_out /*device*/);
+
+/* Device time of each operator of the task's most recent advance call, in milliseconds, when
+ * per-op timing was switched on with fp_prefill_set_timing(task, 1) before that call.  Writes
+ * min(n, ops of that call) entries to ms_out (host) and the count to *n_out.                     */
+fp_status fp_prefill_set_timing(fp_prefill* task, int32_t on);
+fp_status fp_prefill_op_times(fp_prefill* task, float* ms_out /*host*/, int32_t n,
+                              int32_t* n_out /*host*/);
+
+/* Ends a task in any state except while an advance is running: returns its workspace to the
+ * model's cache and frees the KV blocks the library allocated for it.                            */
+void fp_prefill_end(fp_prefill* task);
+
+/* Single-operator entry points used by the unit tests and the roofline measurement: each
+ * launches exactly the kernel the prefill path uses for that operator on `hip_stream` and
+ * returns without synchronising.  Pointers are device pointers; dtype is FP_DTYPE_*.
+ *   fp_op_gemm     C[M,N] (+)= A[M,K] W[N,K]^T.  residual=0: C in the storage dtype is
+ *                  overwritten; residual=1: C is fp32 and accumulated into (x += ...).
+ *   fp_op_rmsnorm  out[T,d] (storage dtype) = rmsnorm(x[T,d] fp32) * gain[d]
+ *   fp_op_silu_mul out[T,F] = silu(gu[:, :F]) * gu[:, F:]
+ * FP_ERR_INVALID on misaligned or non-positive sizes (K and N multiples of 8).                   */
+fp_status fp_op_gemm(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
+                     int64_t k, int32_t residual, void* hip_stream);
+fp_status fp_op_rmsnorm(int32_t dtype, const void* x_f32, const void* gain, void* out,
+                        int64_t t, int64_t d, float eps, void* hip_stream);
+fp_status fp_op_silu_mul(int32_t dtype, const void* gu, void* out, int64_t t, int64_t f,
+                         void* hip_stream);
+
+const char* fp_last_error(void);
+const char* fp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLOWPREFILL_H */

@@ -1,0 +1,366 @@
+// Causal variable-length grouped-query attention over the paged KV cache
+// (FlowPrefill Eq. (2) with the causal mask and KV-cache reuse of Section 3.1; operator `attn`
+// of Section 5.1).  bf16 path: flash-style tiling, MFMA 32x32x16 for both contractions, fp32
+// online softmax.  fp32 path: one wave per (token, head), plain FMAs (debug).
+#include "common.h"
+#include "kernels.h"
+
+namespace fp {
+
+// ------------------------------------------------------------------------------------------
+// bf16 kernel.
+//
+// One workgroup = NW waves = one (sequence, query tile of NW*32*NQ rows, query head).  Keys are
+// consumed 64 at a time (four 16-token cache blocks), staged in LDS, double-buffered.
+//
+// The score tile is computed TRANSPOSED, S^T = K Q^T: the MFMA accumulator layout then gives
+// each lane one query column and 16 key rows per 32-key block, so the row maximum and row sum of
+// the softmax are in-lane reductions plus one exchange with lane^32, the rescale factor is a
+// per-lane scalar, and exp(S^T) converted to bf16 is already laid out as the B operand of the
+// second MFMA, O^T += V^T P^T -- no LDS round trip for P.
+//
+// Accumulator row i = 8a + 4h + b (a = reg/4, h = lane/32, b = reg%4) of a 32-row block, while
+// the B operand wants k = 8h + e.  Loading key pi(i) into MFMA row i, pi = swap of bits 2 and 3,
+// makes registers 8*a1 .. 8*a1+7 of a lane hold the 8 consecutive keys 16*a1 + 8h + (0..7): one
+// B operand per 16-key chunk, matching V^T read in natural key order.
+//
+// LDS layouts (16-byte chunks):
+//   K tile [64 keys][D]      chunk c of key row r stored at c ^ ((r&3) | ((r&8)>>1))
+//   V tile [4 blocks][D][16] the two 16-byte halves of channel row d swapped when d & 4
+// Both make the 8 lanes of a ds_read_b128 phase hit distinct banks.
+// ------------------------------------------------------------------------------------------
+constexpr int kKT = 64;   // keys per tile
+
+template <int D, int NQ, int NW>
+__global__ __launch_bounds__(NW * 64, 1) void attn_bf16_kernel(
+    const bf16* __restrict__ qkv, const bf16* __restrict__ k_pool, const bf16* __restrict__ v_pool,
+    bf16* __restrict__ o, int n_q_heads, int n_kv_heads, int64_t kv_num_blocks, int layer,
+    const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ cached_lens,
+    const int32_t* __restrict__ block_tables, int max_blocks,
+    const int32_t* __restrict__ attn_items, float scale_log2) {
+  static_assert(NW * 64 == 256, "tile loaders assume 256 threads");
+  constexpr int BQW = NW * 32 * NQ;
+  constexpr int CPR = D / 8;                 // 16-byte chunks per key row
+  constexpr int CH = kKvBlock * CPR;         // chunks per 16-token block
+  constexpr int PASSES = 4 * CH / 256;       // per-thread chunks per tile (K and V each)
+  constexpr int DB = D / 32;                 // 32-channel blocks of the output
+  constexpr int KK = D / 16;                 // MFMA k-steps of the score contraction
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16* sK = reinterpret_cast<bf16*>(smem_raw);   // [2][64*D]
+  bf16* sV = sK + 2 * kKT * D;                    // [2][64*D]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lq = lane & 31, lh = lane >> 5;
+  const int group = n_q_heads / n_kv_heads;
+  const int w = blockIdx.x;
+  const int kvh = w % n_kv_heads;
+  const int rest = w / n_kv_heads;
+  const int head = kvh * group + rest % group;
+  const int item = rest / group;
+  const int s = attn_items[2 * item];
+  const int qt = attn_items[2 * item + 1];
+
+  const int seq_lo = cu_seqlens[s];
+  const int n_new = cu_seqlens[s + 1] - seq_lo;
+  const int cached = cached_lens[s];
+  const int total = cached + n_new;
+  const int q_row0 = qt * BQW;
+  const int wq0 = q_row0 + wave * 32 * NQ;
+  const int kv_len = cached + min(n_new, q_row0 + BQW);
+  const int n_tiles = (kv_len + kKT - 1) / kKT;
+  const int64_t width = (int64_t)(n_q_heads + 2 * n_kv_heads) * D;
+  const int32_t* bt = block_tables + (int64_t)s * max_blocks;
+  const int64_t pool_layer = (int64_t)layer * kv_num_blocks;
+
+  // ---- query fragments (B operand of S^T = K Q^T), resident for the whole kernel ----
+  bf16x8 qf[NQ][KK];
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    const int row = min(wq0 + nq * 32 + lq, n_new - 1);
+    const bf16* src = qkv + (int64_t)(seq_lo + row) * width + head * D + lh * 8;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[nq][kk] = *reinterpret_cast<const bf16x8*>(src + kk * 16);
+  }
+
+  f32x16 oacc[DB][NQ];
+#pragma unroll
+  for (int i = 0; i < DB; ++i)
+#pragma unroll
+    for (int j = 0; j < NQ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[i][j][r] = 0.f;
+  float m_run[NQ], l_run[NQ];
+#pragma unroll
+  for (int j = 0; j < NQ; ++j) { m_run[j] = -INFINITY; l_run[j] = 0.f; }
+
+  u32x4 rk[PASSES], rv[PASSES];
+  auto load_tile = [&](int tile) {
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+      const int flat = tid + i * 256;
+      const int c = flat / CH, chunk = flat % CH;
+      const int lb = tile * 4 + c;
+      if (lb * kKvBlock < total) {
+        const int64_t blk = bt[lb];
+        const int64_t base = ((pool_layer + blk) * n_kv_heads + kvh) * (int64_t)(kKvBlock * D);
+        rk[i] = *reinterpret_cast<const u32x4*>(k_pool + base + chunk * 8);
+        rv[i] = *reinterpret_cast<const u32x4*>(v_pool + base + chunk * 8);
+      } else {
+        rk[i] = u32x4{0, 0, 0, 0};
+        rv[i] = u32x4{0, 0, 0, 0};
+      }
+    }
+  };
+  auto store_tile = [&](int buf) {
+    bf16* dK = sK + buf * kKT * D;
+    bf16* dV = sV + buf * kKT * D;
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+      const int flat = tid + i * 256;
+      const int c = flat / CH, chunk = flat % CH;
+      const int key = chunk / CPR, dch = chunk % CPR;
+      const int row = c * kKvBlock + key;
+      const int swz = (row & 3) | ((row & 8) >> 1);
+      *reinterpret_cast<u32x4*>(dK + row * D + ((dch ^ swz) << 3)) = rk[i];
+      const int d = chunk >> 1, half = chunk & 1;
+      const int phys = d * 2 + (half ^ ((d >> 2) & 1));
+      *reinterpret_cast<u32x4*>(dV + c * (D * kKvBlock) + (phys << 3)) = rv[i];
+    }
+  };
+
+  if (n_tiles > 0) {
+    load_tile(0);
+    store_tile(0);
+  }
+  __syncthreads();
+
+  const int wave_q_min = cached + wq0;                    // smallest query position of the wave
+  const int wave_q_max = cached + wq0 + 32 * NQ - 1;      // largest
+  const int pi_row = (lq & ~12) | ((lq & 4) << 1) | ((lq & 8) >> 1);
+  const int k_swz = lq & 7;
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const int cur = t & 1;
+    if (t + 1 < n_tiles) load_tile(t + 1);
+    const int key0 = t * kKT;
+    if (key0 <= wave_q_max && wq0 < n_new) {
+      const bf16* cK = sK + cur * kKT * D;
+      const bf16* cV = sV + cur * kKT * D;
+      // ---- S^T = K Q^T ----
+      f32x16 sacc[2][NQ];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+        for (int j = 0; j < NQ; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sacc[rb][j][r] = 0.f;
+        const bf16* krow = cK + (rb * 32 + pi_row) * D;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          const int dch = kk * 2 + lh;
+          bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + ((dch ^ k_swz) << 3));
+#pragma unroll
+          for (int j = 0; j < NQ; ++j)
+            sacc[rb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[j][kk], sacc[rb][j], 0, 0, 0);
+        }
+      }
+      // ---- online softmax, per query column ----
+      const bool need_mask = key0 + kKT - 1 > wave_q_min;
+      bf16x8 pf[NQ][4];
+#pragma unroll
+      for (int j = 0; j < NQ; ++j) {
+        const int qpos = cached + wq0 + j * 32 + lq;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float x = sacc[rb][j][r] * scale_log2;
+            if (need_mask) {
+              const int key = key0 + rb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
+              x = key <= qpos ? x : -INFINITY;
+            }
+            sacc[rb][j][r] = x;
+            mx = fmaxf(mx, x);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run[j], mx);
+        // m_new is finite from the first tile on: key 0 is visible to every query.
+        const float alpha = __builtin_amdgcn_exp2f(m_run[j] - m_new);
+        m_run[j] = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_exp2f(sacc[rb][j][r] - m_new);
+            sacc[rb][j][r] = p;
+            psum += p;
+          }
+        l_run[j] = l_run[j] * alpha + psum;
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[i][j][r] *= alpha;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          f32x8 pv;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) pv[e] = sacc[c >> 1][j][8 * (c & 1) + e];
+          pf[j][c] = __builtin_convertvector(pv, bf16x8);
+        }
+      }
+      // ---- O^T += V^T P^T ----
+#pragma unroll
+      for (int i = 0; i < DB; ++i) {
+        const int d = i * 32 + lq;
+        const int phys = d * 2 + (lh ^ ((d >> 2) & 1));
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          bf16x8 vf = *reinterpret_cast<const bf16x8*>(cV + c * (D * kKvBlock) + (phys << 3));
+#pragma unroll
+          for (int j = 0; j < NQ; ++j)
+            oacc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[j][c], oacc[i][j], 0, 0, 0);
+        }
+      }
+    }
+    if (t + 1 < n_tiles) store_tile(cur ^ 1);
+    __syncthreads();
+  }
+
+  // ---- normalise, stage through LDS, store rows with 16-byte accesses ----
+  bf16* stage = reinterpret_cast<bf16*>(smem_raw) + wave * (32 * NQ * D);
+#pragma unroll
+  for (int j = 0; j < NQ; ++j) {
+    const float l_tot = l_run[j] + __shfl_xor(l_run[j], 32, 64);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    const int row = j * 32 + lq;
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int d = i * 32 + 8 * a + 4 * lh;
+        bf16x4 v4;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) v4[b] = static_cast<bf16>(oacc[i][j][4 * a + b] * inv);
+        const int dch = d >> 3;
+        *reinterpret_cast<bf16x4*>(stage + row * D + ((dch ^ (row & 7)) << 3) + (d & 7)) = v4;
+      }
+  }
+  __syncthreads();
+  const int64_t o_width = (int64_t)n_q_heads * D;
+#pragma unroll
+  for (int i = 0; i < 32 * NQ * CPR / 64; ++i) {
+    const int idx = lane + i * 64;
+    const int row = idx / CPR, dch = idx % CPR;
+    if (wq0 + row < n_new) {
+      u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * D + ((dch ^ (row & 7)) << 3));
+      *reinterpret_cast<u32x4*>(o + (int64_t)(seq_lo + wq0 + row) * o_width + head * D + dch * 8) = v;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// fp32 debug kernel: one wave per (token, query head).  Lane l walks keys l, l+64, ... keeping
+// its own running max / sum / weighted value sum; the 64 partial states are merged at the end.
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void attn_f32_kernel(
+    const float* __restrict__ qkv, const float* __restrict__ k_pool,
+    const float* __restrict__ v_pool, float* __restrict__ o, int n_q_heads, int n_kv_heads,
+    int64_t kv_num_blocks, int layer, const int32_t* __restrict__ tok_seq,
+    const int32_t* __restrict__ tok_pos, const int32_t* __restrict__ block_tables, int max_blocks,
+    float scale) {
+  const int t = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+  const int s = tok_seq[t], pos = tok_pos[t];
+  const int kvh = head / (n_q_heads / n_kv_heads);
+  const int64_t width = (int64_t)(n_q_heads + 2 * n_kv_heads) * D;
+  const float* q = qkv + (int64_t)t * width + head * D;
+  const int32_t* bt = block_tables + (int64_t)s * max_blocks;
+  float qv[D];
+#pragma unroll
+  for (int d = 0; d < D; ++d) qv[d] = q[d];
+  float acc[D];
+#pragma unroll
+  for (int d = 0; d < D; ++d) acc[d] = 0.f;
+  float m = -INFINITY, l = 0.f;
+  for (int key = lane; key <= pos; key += 64) {
+    const int64_t blk = bt[key / kKvBlock];
+    const int64_t base = (((int64_t)layer * kv_num_blocks + blk) * n_kv_heads + kvh) *
+                         (int64_t)(kKvBlock * D);
+    const float* kr = k_pool + base + (key % kKvBlock) * D;
+    float sc = 0.f;
+#pragma unroll
+    for (int d = 0; d < D; ++d) sc = fmaf(qv[d], kr[d], sc);
+    sc *= scale;
+    const float m_new = fmaxf(m, sc);
+    const float alpha = __expf(m - m_new);
+    const float p = __expf(sc - m_new);
+    l = l * alpha + p;
+    const float* vr = v_pool + base + (key % kKvBlock);
+#pragma unroll
+    for (int d = 0; d < D; ++d) acc[d] = acc[d] * alpha + p * vr[d * kKvBlock];
+    m = m_new;
+  }
+  const float m_all = wave_max(m);
+  const float w = (m == -INFINITY) ? 0.f : __expf(m - m_all);
+  const float l_all = wave_sum(l * w);
+  float* orow = o + (int64_t)t * n_q_heads * D + head * D;
+#pragma unroll
+  for (int d = 0; d < D; ++d) {
+    const float v = wave_sum(acc[d] * w);
+    if (lane == 0) orow[d] = v / l_all;
+  }
+}
+
+int attention_q_tile_rows(int head_dim) { (void)head_dim; return 4 * 32 * 2; }
+
+template <int D>
+static void launch_attn_bf16(const void* qkv, const void* k_pool, const void* v_pool, void* o,
+                             const Geometry& g, const BatchMeta& m, int layer, hipStream_t s) {
+  constexpr int NQ = 2, NW = 4;
+  const size_t smem = (size_t)4 * kKT * D * sizeof(bf16);
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, NQ, NW>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    attr_set = true;
+  }
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)D);
+  dim3 grid((unsigned)((int64_t)m.n_attn_items * g.n_q_heads));
+  attn_bf16_kernel<D, NQ, NW><<<grid, NW * 64, smem, s>>>(
+      (const bf16*)qkv, (const bf16*)k_pool, (const bf16*)v_pool, (bf16*)o, g.n_q_heads,
+      g.n_kv_heads, g.kv_num_blocks, layer, m.cu_seqlens, m.cached_lens, m.block_tables,
+      m.max_blocks, m.attn_items, scale_log2);
+}
+
+template <int D>
+static void launch_attn_f32(const void* qkv, const void* k_pool, const void* v_pool, void* o,
+                            const Geometry& g, const BatchMeta& m, int layer, hipStream_t s) {
+  dim3 grid((unsigned)m.n_tokens, (unsigned)g.n_q_heads);
+  attn_f32_kernel<D><<<grid, 64, 0, s>>>((const float*)qkv, (const float*)k_pool,
+                                         (const float*)v_pool, (float*)o, g.n_q_heads,
+                                         g.n_kv_heads, g.kv_num_blocks, layer, m.tok_seq,
+                                         m.tok_pos, m.block_tables, m.max_blocks,
+                                         1.0f / sqrtf((float)D));
+}
+
+void launch_attention(int dtype, const void* qkv, const void* k_pool, const void* v_pool,
+                      void* o, const Geometry& g, const BatchMeta& m, int layer, hipStream_t s) {
+  if (m.n_tokens == 0) return;
+  if (dtype == 1) {
+    if (m.n_attn_items == 0) return;
+    if (g.head_dim == 128) launch_attn_bf16<128>(qkv, k_pool, v_pool, o, g, m, layer, s);
+    else launch_attn_bf16<64>(qkv, k_pool, v_pool, o, g, m, layer, s);
+  } else {
+    switch (g.head_dim) {
+      case 16: launch_attn_f32<16>(qkv, k_pool, v_pool, o, g, m, layer, s); break;
+      case 32: launch_attn_f32<32>(qkv, k_pool, v_pool, o, g, m, layer, s); break;
+      case 64: launch_attn_f32<64>(qkv, k_pool, v_pool, o, g, m, layer, s); break;
+      default: launch_attn_f32<128>(qkv, k_pool, v_pool, o, g, m, layer, s); break;
+    }
+  }
+}
+
+}  // namespace fp

@@ -1,0 +1,56 @@
+// Host-callable launchers of the prefill operators.  Each launches on the given stream and
+// returns without synchronising; hipGetLastError is left for the caller to check.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fp {
+
+// Static geometry of the model that the kernels need.
+struct Geometry {
+  int32_t hidden, n_q_heads, n_kv_heads, head_dim, ffn;
+  int64_t kv_num_blocks;
+  int32_t qkv_width() const { return (n_q_heads + 2 * n_kv_heads) * head_dim; }
+};
+
+// Per-task device-side description of the packed batch.
+struct BatchMeta {
+  int32_t n_tokens;             // T
+  int32_t n_seqs;
+  int32_t max_blocks;           // row length of block_tables
+  const int32_t* tok_seq;       // device [T]   sequence of each packed token
+  const int32_t* tok_pos;       // device [T]   absolute position (cached_len + index in chunk)
+  const int32_t* cu_seqlens;    // device [n_seqs+1]
+  const int32_t* cached_lens;   // device [n_seqs]
+  const int32_t* block_tables;  // device [n_seqs, max_blocks]
+  const int32_t* kv_items;      // device [n_kv_items][2]  (seq, logical block) touched by new tokens
+  int32_t n_kv_items;
+  const int32_t* attn_items;    // device [n_attn_items][2] (seq, query tile), longest first
+  int32_t n_attn_items;
+};
+
+// Rows of queries one attention workgroup owns on the bf16 path (the runtime sizes attn_items
+// with it).
+int attention_q_tile_rows(int head_dim);
+
+void launch_to_residual(int dtype, const void* in, float* x, int64_t n_elems, hipStream_t s);
+void launch_rmsnorm(int dtype, const float* x, const void* gain, void* out, int64_t t, int64_t d,
+                    float eps, hipStream_t s);
+void launch_silu_mul(int dtype, const void* gu, void* out, int64_t t, int64_t f, hipStream_t s);
+// qkv [T, qkv_width] in place for the query columns; rotated keys and raw values go to the pools.
+void launch_rope_kvwrite(int dtype, void* qkv, const float* rope_cos, const float* rope_sin,
+                         const Geometry& g, const BatchMeta& m, int layer, void* k_pool,
+                         void* v_pool, hipStream_t s);
+void launch_attention(int dtype, const void* qkv, const void* k_pool, const void* v_pool,
+                      void* o, const Geometry& g, const BatchMeta& m, int layer, hipStream_t s);
+// C[M,N] = A[M,K] W[N,K]^T  (residual == 0, C in the storage dtype), or C_f32 += ... (residual).
+void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
+                 int64_t k, int residual, hipStream_t s);
+
+// Gathers positions 0..len-1 of one sequence (block table row `table_dev`, device) of one layer
+// into contiguous k_out/v_out [len, Hkv, D].
+void launch_kv_gather(int dtype, const void* k_pool, const void* v_pool, void* k_out, void* v_out,
+                      int len, const Geometry& g, int layer, const int32_t* table_dev,
+                      hipStream_t s);
+
+}  // namespace fp

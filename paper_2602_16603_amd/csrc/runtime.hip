@@ -1,0 +1,675 @@
+// Host runtime behind the C ABI: model (weights, RoPE table, paged KV pool, block allocator,
+// workspace cache), execution task (operator cursor, per-task workspace, preemption gate) and
+// the extern "C" entry points.
+//
+// FlowPrefill Section 5.1: a task runs operator by operator; between operators the runtime
+// looks at a signal the scheduler may have set; if set it lets the work in flight finish,
+// clears the signal, acknowledges and suspends the task with all of its state left in place.
+// Section 4: the execution pool keeps the state of preempted tasks until they are resumed.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <climits>
+#include <cmath>
+#include <condition_variable>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/flowprefill.h"
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+fp_status fail(fp_status code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return code;
+}
+
+#define FP_HIP(call)                                                                     \
+  do {                                                                                   \
+    hipError_t e_ = (call);                                                              \
+    if (e_ != hipSuccess)                                                                \
+      return fail(e_ == hipErrorOutOfMemory ? FP_ERR_OOM : FP_ERR_DEVICE, "%s: %s", #call, \
+                  hipGetErrorString(e_));                                                \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Workspace {
+  void* base = nullptr;
+  size_t bytes = 0;
+};
+
+enum class TaskState { Idle, Running, Parked, Done };
+
+constexpr int kEventRing = 8;
+
+}  // namespace
+
+struct fp_model {
+  fp_shape shape;
+  fp::Geometry geo;
+  hipStream_t stream = nullptr;
+  size_t elem = 2;
+  std::vector<fp_layer_weights> layers;
+  float* rope_cos = nullptr;
+  float* rope_sin = nullptr;
+  void* k_pool = nullptr;
+  void* v_pool = nullptr;
+  std::mutex mu;                       // guards free_blocks, ws_cache, live_tasks
+  std::vector<int32_t> free_blocks;    // stack of free physical block ids
+  std::vector<uint8_t> block_used;
+  std::vector<Workspace> ws_cache;
+  int live_tasks = 0;
+};
+
+struct fp_prefill {
+  fp_model* model = nullptr;
+  int32_t n_tokens = 0, n_seqs = 0, max_blocks = 0;
+  uint32_t boundary_mask = FP_BOUNDARY_EVERY_OP;
+  std::vector<int32_t> cu, cached, tables, owned_blocks;
+  Workspace ws;
+  // carved out of ws:
+  float* x = nullptr;
+  void *h = nullptr, *qkv = nullptr, *o = nullptr, *gu = nullptr, *act = nullptr;
+  fp::BatchMeta meta{};
+  // cursor and gate
+  int32_t cursor = 0;                  // next operator, 0 .. n_layers*9
+  int32_t launch_ahead = 2;
+  std::mutex mu;
+  std::condition_variable cv;
+  TaskState state = TaskState::Idle;
+  std::atomic<int> signal{0};
+  hipEvent_t ring[kEventRing] = {};
+  // per-op timing
+  bool timing = false;
+  std::vector<hipEvent_t> tev;
+  int32_t timed_ops = 0;
+};
+
+namespace {
+
+fp_status launch_op(fp_prefill* t, int32_t index) {
+  fp_model* m = t->model;
+  const fp_shape& sh = m->shape;
+  const int layer = index / FP_OPS_PER_LAYER, op = index % FP_OPS_PER_LAYER;
+  const fp_layer_weights& w = m->layers[layer];
+  const int dt = sh.dtype;
+  const int64_t T = t->n_tokens, d = sh.hidden, F = sh.ffn;
+  const int64_t qd = (int64_t)sh.n_q_heads * sh.head_dim;
+  hipStream_t s = m->stream;
+  switch (op) {
+    case 0: fp::launch_rmsnorm(dt, t->x, w.attn_norm, t->h, T, d, sh.rms_eps, s); break;
+    case 1: fp::launch_gemm(dt, t->h, w.w_qkv, t->qkv, T, m->geo.qkv_width(), d, 0, s); break;
+    case 2:
+      fp::launch_rope_kvwrite(dt, t->qkv, m->rope_cos, m->rope_sin, m->geo, t->meta, layer,
+                              m->k_pool, m->v_pool, s);
+      break;
+    case 3:
+      fp::launch_attention(dt, t->qkv, m->k_pool, m->v_pool, t->o, m->geo, t->meta, layer, s);
+      break;
+    case 4: fp::launch_gemm(dt, t->o, w.w_o, t->x, T, d, qd, 1, s); break;
+    case 5: fp::launch_rmsnorm(dt, t->x, w.mlp_norm, t->h, T, d, sh.rms_eps, s); break;
+    case 6: fp::launch_gemm(dt, t->h, w.w_gate_up, t->gu, T, 2 * F, d, 0, s); break;
+    case 7: fp::launch_silu_mul(dt, t->gu, t->act, T, F, s); break;
+    case 8: fp::launch_gemm(dt, t->act, w.w_down, t->x, T, d, F, 1, s); break;
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess)
+    return fail(FP_ERR_DEVICE, "launch of layer %d op %d failed: %s", layer, op,
+                hipGetErrorString(e));
+  return FP_OK;
+}
+
+fp_status acquire_workspace(fp_model* m, size_t bytes, Workspace* out) {
+  {
+    std::lock_guard<std::mutex> lk(m->mu);
+    int best = -1;
+    for (int i = 0; i < (int)m->ws_cache.size(); ++i)
+      if (m->ws_cache[i].bytes >= bytes && (best < 0 || m->ws_cache[i].bytes < m->ws_cache[best].bytes))
+        best = i;
+    if (best >= 0) {
+      *out = m->ws_cache[best];
+      m->ws_cache.erase(m->ws_cache.begin() + best);
+      return FP_OK;
+    }
+  }
+  void* p = nullptr;
+  FP_HIP(hipMalloc(&p, bytes));
+  out->base = p;
+  out->bytes = bytes;
+  return FP_OK;
+}
+
+void release_workspace(fp_model* m, Workspace ws) {
+  if (!ws.base) return;
+  std::lock_guard<std::mutex> lk(m->mu);
+  m->ws_cache.push_back(ws);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fp_last_error(void) { return g_last_error.c_str(); }
+const char* fp_version(void) { return "flowprefill-gfx950 0.1"; }
+
+fp_status fp_model_create(const fp_shape* shape, const fp_layer_weights* layers, void* hip_stream,
+                          fp_model** out) {
+  if (!shape || !layers || !out) return fail(FP_ERR_INVALID, "null argument");
+  const fp_shape& s = *shape;
+  if (s.n_layers <= 0 || s.hidden <= 0 || s.n_q_heads <= 0 || s.n_kv_heads <= 0 ||
+      s.head_dim <= 0 || s.ffn <= 0 || s.kv_num_blocks <= 0 || s.max_position <= 0)
+    return fail(FP_ERR_INVALID, "non-positive shape field");
+  if (s.dtype != FP_DTYPE_F32 && s.dtype != FP_DTYPE_BF16)
+    return fail(FP_ERR_INVALID, "dtype must be 0 (fp32) or 1 (bf16)");
+  if (s.kv_block_tokens != fp::kKvBlock) return fail(FP_ERR_INVALID, "kv_block_tokens must be 16");
+  if (s.n_q_heads % s.n_kv_heads) return fail(FP_ERR_INVALID, "n_q_heads not a multiple of n_kv_heads");
+  if (s.hidden % 8 || s.ffn % 8 || s.head_dim % 16)
+    return fail(FP_ERR_INVALID, "hidden and ffn must be multiples of 8, head_dim of 16");
+  if (s.dtype == FP_DTYPE_BF16 && s.head_dim != 64 && s.head_dim != 128)
+    return fail(FP_ERR_INVALID, "bf16 path supports head_dim 64 or 128");
+  if (s.dtype == FP_DTYPE_F32 && s.head_dim != 16 && s.head_dim != 32 && s.head_dim != 64 &&
+      s.head_dim != 128)
+    return fail(FP_ERR_INVALID, "fp32 path supports head_dim 16, 32, 64 or 128");
+  if (s.kv_num_blocks > INT32_MAX) return fail(FP_ERR_INVALID, "kv_num_blocks too large");
+  for (int l = 0; l < s.n_layers; ++l) {
+    const void* ptrs[6] = {layers[l].attn_norm, layers[l].w_qkv, layers[l].w_o,
+                           layers[l].mlp_norm, layers[l].w_gate_up, layers[l].w_down};
+    for (const void* p : ptrs)
+      if (!p || (reinterpret_cast<uintptr_t>(p) & 15))
+        return fail(FP_ERR_INVALID, "layer %d: null or misaligned weight pointer", l);
+  }
+  fp_model* m = new (std::nothrow) fp_model();
+  if (!m) return fail(FP_ERR_OOM, "host allocation failed");
+  m->shape = s;
+  m->geo = fp::Geometry{s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn, s.kv_num_blocks};
+  m->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  m->elem = s.dtype == FP_DTYPE_BF16 ? 2 : 4;
+  m->layers.assign(layers, layers + s.n_layers);
+
+  // RoPE table: angle = p * theta^(-2j/D), evaluated in fp64 and rounded once to fp32.
+  const int half = s.head_dim / 2;
+  std::vector<float> hc((size_t)s.max_position * half), hs((size_t)s.max_position * half);
+  std::vector<double> inv_freq(half);
+  for (int j = 0; j < half; ++j)
+    inv_freq[j] = std::pow((double)s.rope_theta, -2.0 * (double)j / (double)s.head_dim);
+  for (int64_t p = 0; p < s.max_position; ++p)
+    for (int j = 0; j < half; ++j) {
+      const double ang = (double)p * inv_freq[j];
+      hc[(size_t)p * half + j] = (float)std::cos(ang);
+      hs[(size_t)p * half + j] = (float)std::sin(ang);
+    }
+  const size_t tbytes = hc.size() * sizeof(float);
+  const size_t pool_bytes = (size_t)s.n_layers * (size_t)s.kv_num_blocks * s.n_kv_heads *
+                            fp::kKvBlock * s.head_dim * m->elem;
+  auto cleanup = [&]() {
+    (void)hipFree(m->rope_cos); (void)hipFree(m->rope_sin);
+    (void)hipFree(m->k_pool); (void)hipFree(m->v_pool);
+    delete m;
+  };
+  hipError_t e;
+  if ((e = hipMalloc((void**)&m->rope_cos, tbytes)) != hipSuccess ||
+      (e = hipMalloc((void**)&m->rope_sin, tbytes)) != hipSuccess ||
+      (e = hipMalloc(&m->k_pool, pool_bytes)) != hipSuccess ||
+      (e = hipMalloc(&m->v_pool, pool_bytes)) != hipSuccess) {
+    cleanup();
+    return fail(e == hipErrorOutOfMemory ? FP_ERR_OOM : FP_ERR_DEVICE, "model allocation: %s",
+                hipGetErrorString(e));
+  }
+  // The pools start at zero so that never-written slots of a partially filled block hold finite
+  // values (the attention kernel multiplies them by an exact zero weight).
+  if ((e = hipMemcpy(m->rope_cos, hc.data(), tbytes, hipMemcpyHostToDevice)) != hipSuccess ||
+      (e = hipMemcpy(m->rope_sin, hs.data(), tbytes, hipMemcpyHostToDevice)) != hipSuccess ||
+      (e = hipMemset(m->k_pool, 0, pool_bytes)) != hipSuccess ||
+      (e = hipMemset(m->v_pool, 0, pool_bytes)) != hipSuccess ||
+      (e = hipDeviceSynchronize()) != hipSuccess) {
+    cleanup();
+    return fail(FP_ERR_DEVICE, "model initialisation: %s", hipGetErrorString(e));
+  }
+  m->free_blocks.resize((size_t)s.kv_num_blocks);
+  for (int64_t i = 0; i < s.kv_num_blocks; ++i)
+    m->free_blocks[(size_t)i] = (int32_t)(s.kv_num_blocks - 1 - i);   // pop gives 0,1,2,...
+  m->block_used.assign((size_t)s.kv_num_blocks, 0);
+  *out = m;
+  return FP_OK;
+}
+
+void fp_model_destroy(fp_model* m) {
+  if (!m) return;
+  (void)hipStreamSynchronize(m->stream);
+  for (auto& ws : m->ws_cache) (void)hipFree(ws.base);
+  (void)hipFree(m->rope_cos);
+  (void)hipFree(m->rope_sin);
+  (void)hipFree(m->k_pool);
+  (void)hipFree(m->v_pool);
+  delete m;
+}
+
+fp_status fp_kv_alloc(fp_model* m, int32_t n, int32_t* ids_out) {
+  if (!m || n < 0 || (n > 0 && !ids_out)) return fail(FP_ERR_INVALID, "bad argument");
+  std::lock_guard<std::mutex> lk(m->mu);
+  if ((size_t)n > m->free_blocks.size())
+    return fail(FP_ERR_OOM, "KV pool exhausted: %d blocks wanted, %zu free", n, m->free_blocks.size());
+  for (int i = 0; i < n; ++i) {
+    ids_out[i] = m->free_blocks.back();
+    m->free_blocks.pop_back();
+    m->block_used[(size_t)ids_out[i]] = 1;
+  }
+  return FP_OK;
+}
+
+fp_status fp_kv_free(fp_model* m, int32_t n, const int32_t* ids) {
+  if (!m || n < 0 || (n > 0 && !ids)) return fail(FP_ERR_INVALID, "bad argument");
+  std::lock_guard<std::mutex> lk(m->mu);
+  for (int i = 0; i < n; ++i)
+    if (ids[i] < 0 || ids[i] >= m->shape.kv_num_blocks || !m->block_used[(size_t)ids[i]])
+      return fail(FP_ERR_INVALID, "block %d is not allocated", ids[i]);
+  for (int i = 0; i < n; ++i) {
+    m->block_used[(size_t)ids[i]] = 0;
+    m->free_blocks.push_back(ids[i]);
+  }
+  return FP_OK;
+}
+
+fp_status fp_model_kv_pools(const fp_model* m, const void** k_pool, const void** v_pool) {
+  if (!m || !k_pool || !v_pool) return fail(FP_ERR_INVALID, "null argument");
+  *k_pool = m->k_pool;
+  *v_pool = m->v_pool;
+  return FP_OK;
+}
+
+fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu_seqlens,
+                           int32_t n_seqs, const int32_t* cached_lens, const int32_t* block_tables,
+                           int32_t max_blocks, uint32_t boundary_mask, fp_prefill** out) {
+  if (!m || !cu_seqlens || !out || n_seqs < 0) return fail(FP_ERR_INVALID, "null or negative argument");
+  if (cu_seqlens[0] != 0) return fail(FP_ERR_INVALID, "cu_seqlens[0] must be 0");
+  for (int s = 0; s < n_seqs; ++s)
+    if (cu_seqlens[s + 1] < cu_seqlens[s]) return fail(FP_ERR_INVALID, "cu_seqlens decreases at %d", s);
+  const int32_t T = cu_seqlens[n_seqs];
+  if (T > 0 && (!hidden_in || (reinterpret_cast<uintptr_t>(hidden_in) & 15)))
+    return fail(FP_ERR_INVALID, "hidden_in null or not 16-byte aligned");
+  if (!block_tables && cached_lens)
+    for (int s = 0; s < n_seqs; ++s)
+      if (cached_lens[s] != 0)
+        return fail(FP_ERR_INVALID, "cached_lens needs caller-provided block_tables");
+  if (block_tables && max_blocks <= 0) return fail(FP_ERR_INVALID, "max_blocks must be positive");
+  const fp_shape& sh = m->shape;
+
+  fp_prefill* t = new (std::nothrow) fp_prefill();
+  if (!t) return fail(FP_ERR_OOM, "host allocation failed");
+  t->model = m;
+  t->n_tokens = T;
+  t->n_seqs = n_seqs;
+  t->boundary_mask = boundary_mask & FP_BOUNDARY_EVERY_OP;
+  t->cu.assign(cu_seqlens, cu_seqlens + n_seqs + 1);
+  t->cached.assign((size_t)n_seqs, 0);
+  if (cached_lens) t->cached.assign(cached_lens, cached_lens + n_seqs);
+
+  std::vector<int32_t> need((size_t)n_seqs, 0);
+  int32_t need_max = 1;
+  for (int s = 0; s < n_seqs; ++s) {
+    const int64_t len = (int64_t)t->cached[s] + (t->cu[s + 1] - t->cu[s]);
+    if (t->cached[s] < 0 || len > sh.max_position) {
+      delete t;
+      return fail(FP_ERR_INVALID, "sequence %d: %lld positions exceed max_position %d", s,
+                  (long long)len, sh.max_position);
+    }
+    need[s] = (int32_t)((len + fp::kKvBlock - 1) / fp::kKvBlock);
+    need_max = std::max(need_max, need[s]);
+  }
+  if (block_tables) {
+    if (max_blocks < need_max && T > 0) {
+      delete t;
+      return fail(FP_ERR_INVALID, "max_blocks %d < %d blocks needed", max_blocks, need_max);
+    }
+    t->max_blocks = max_blocks;
+    t->tables.assign(block_tables, block_tables + (size_t)n_seqs * max_blocks);
+    for (int s = 0; s < n_seqs; ++s)
+      for (int b = 0; b < need[s]; ++b) {
+        const int32_t id = t->tables[(size_t)s * max_blocks + b];
+        if (id < 0 || id >= sh.kv_num_blocks) {
+          delete t;
+          return fail(FP_ERR_INVALID, "sequence %d block %d: id %d outside the pool", s, b, id);
+        }
+      }
+  } else {
+    t->max_blocks = need_max;
+    t->tables.assign((size_t)n_seqs * need_max, -1);
+    int64_t total = 0;
+    for (int s = 0; s < n_seqs; ++s) total += need[s];
+    t->owned_blocks.resize((size_t)total);
+    fp_status st = fp_kv_alloc(m, (int32_t)total, t->owned_blocks.data());
+    if (st != FP_OK) { delete t; return st; }
+    size_t at = 0;
+    for (int s = 0; s < n_seqs; ++s)
+      for (int b = 0; b < need[s]; ++b) t->tables[(size_t)s * need_max + b] = t->owned_blocks[at++];
+  }
+
+  // ---- host-side work lists ----
+  const int bqw = fp::attention_q_tile_rows(sh.head_dim);
+  std::vector<int32_t> tok_seq((size_t)T), tok_pos((size_t)T), kv_items, attn_items;
+  struct Item { int32_t seq, qt, work; };
+  std::vector<Item> items;
+  for (int s = 0; s < n_seqs; ++s) {
+    const int32_t lo = t->cu[s], n = t->cu[s + 1] - lo, c = t->cached[s];
+    for (int i = 0; i < n; ++i) { tok_seq[(size_t)lo + i] = s; tok_pos[(size_t)lo + i] = c + i; }
+    if (n == 0) continue;
+    for (int32_t lb = c / fp::kKvBlock; lb <= (c + n - 1) / fp::kKvBlock; ++lb) {
+      kv_items.push_back(s);
+      kv_items.push_back(lb);
+    }
+    for (int32_t qt = 0; qt * bqw < n; ++qt) {
+      const int32_t kv_len = c + std::min(n, (qt + 1) * bqw);
+      items.push_back(Item{s, qt, (kv_len + 63) / 64});
+    }
+  }
+  // Longest first: workgroups are dispatched in index order, so the heaviest causal tiles
+  // start first and the short ones fill the tail.
+  std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.work > b.work; });
+  for (const Item& it : items) { attn_items.push_back(it.seq); attn_items.push_back(it.qt); }
+
+  // ---- workspace layout ----
+  const size_t e = m->elem;
+  const size_t d = sh.hidden, W = (size_t)m->geo.qkv_width(), qd = (size_t)sh.n_q_heads * sh.head_dim,
+               F = sh.ffn;
+  const size_t Tn = (size_t)std::max(T, 1);
+  size_t off = 0;
+  auto carve = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  const size_t o_x = carve(Tn * d * 4), o_h = carve(Tn * d * e), o_qkv = carve(Tn * W * e),
+               o_o = carve(Tn * qd * e), o_gu = carve(Tn * 2 * F * e), o_act = carve(Tn * F * e);
+  const size_t n_int = tok_seq.size() + tok_pos.size() + t->cu.size() + t->cached.size() +
+                       t->tables.size() + kv_items.size() + attn_items.size();
+  const size_t o_int = carve((n_int + 16) * 4);
+  fp_status st = acquire_workspace(m, off, &t->ws);
+  if (st != FP_OK) {
+    if (!t->owned_blocks.empty()) fp_kv_free(m, (int32_t)t->owned_blocks.size(), t->owned_blocks.data());
+    delete t;
+    return st;
+  }
+  char* base = static_cast<char*>(t->ws.base);
+  t->x = reinterpret_cast<float*>(base + o_x);
+  t->h = base + o_h; t->qkv = base + o_qkv; t->o = base + o_o; t->gu = base + o_gu; t->act = base + o_act;
+
+  std::vector<int32_t> ints;
+  ints.reserve(n_int);
+  auto put = [&](const std::vector<int32_t>& v) { size_t at = ints.size(); ints.insert(ints.end(), v.begin(), v.end()); return at; };
+  const size_t a_seq = put(tok_seq), a_pos = put(tok_pos), a_cu = put(t->cu), a_cached = put(t->cached),
+               a_tab = put(t->tables), a_kv = put(kv_items), a_attn = put(attn_items);
+  int32_t* dints = reinterpret_cast<int32_t*>(base + o_int);
+  auto bail = [&](fp_status code) {
+    release_workspace(m, t->ws);
+    if (!t->owned_blocks.empty()) fp_kv_free(m, (int32_t)t->owned_blocks.size(), t->owned_blocks.data());
+    for (auto& ev : t->ring) if (ev) (void)hipEventDestroy(ev);
+    delete t;
+    return code;
+  };
+  hipError_t he;
+  if (!ints.empty() &&
+      (he = hipMemcpyAsync(dints, ints.data(), ints.size() * 4, hipMemcpyHostToDevice, m->stream)) != hipSuccess)
+    return bail(fail(FP_ERR_DEVICE, "metadata upload: %s", hipGetErrorString(he)));
+  t->meta.n_tokens = T;
+  t->meta.n_seqs = n_seqs;
+  t->meta.max_blocks = t->max_blocks;
+  t->meta.tok_seq = dints + a_seq;
+  t->meta.tok_pos = dints + a_pos;
+  t->meta.cu_seqlens = dints + a_cu;
+  t->meta.cached_lens = dints + a_cached;
+  t->meta.block_tables = dints + a_tab;
+  t->meta.kv_items = dints + a_kv;
+  t->meta.n_kv_items = (int32_t)(kv_items.size() / 2);
+  t->meta.attn_items = dints + a_attn;
+  t->meta.n_attn_items = (int32_t)(attn_items.size() / 2);
+
+  fp::launch_to_residual(sh.dtype, hidden_in, t->x, (int64_t)T * sh.hidden, m->stream);
+  if ((he = hipGetLastError()) != hipSuccess || (he = hipStreamSynchronize(m->stream)) != hipSuccess)
+    return bail(fail(FP_ERR_DEVICE, "residual initialisation: %s", hipGetErrorString(he)));
+  for (auto& ev : t->ring)
+    if ((he = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess)
+      return bail(fail(FP_ERR_DEVICE, "event creation: %s", hipGetErrorString(he)));
+  {
+    std::lock_guard<std::mutex> lk(m->mu);
+    m->live_tasks++;
+  }
+  *out = t;
+  return FP_OK;
+}
+
+fp_status fp_prefill_set_launch_ahead(fp_prefill* t, int32_t k) {
+  if (!t || k < 1 || k > kEventRing) return fail(FP_ERR_INVALID, "launch_ahead must be 1..%d", kEventRing);
+  std::lock_guard<std::mutex> lk(t->mu);
+  if (t->state == TaskState::Running) return fail(FP_ERR_STATE, "task is running");
+  t->launch_ahead = k;
+  return FP_OK;
+}
+
+fp_status fp_prefill_set_timing(fp_prefill* t, int32_t on) {
+  if (!t) return fail(FP_ERR_INVALID, "null task");
+  std::lock_guard<std::mutex> lk(t->mu);
+  if (t->state == TaskState::Running) return fail(FP_ERR_STATE, "task is running");
+  t->timing = on != 0;
+  return FP_OK;
+}
+
+fp_status fp_prefill_advance(fp_prefill* t, int32_t max_ops, int32_t* ops_done) {
+  if (!t || max_ops < 0) return fail(FP_ERR_INVALID, "bad argument");
+  if (ops_done) *ops_done = 0;
+  const int32_t total = t->model->shape.n_layers * FP_OPS_PER_LAYER;
+  {
+    std::lock_guard<std::mutex> lk(t->mu);
+    if (t->state != TaskState::Idle)
+      return fail(FP_ERR_STATE, "advance on a task that is %s",
+                  t->state == TaskState::Parked ? "parked" : t->state == TaskState::Done ? "done" : "running");
+    t->state = TaskState::Running;
+  }
+  hipStream_t s = t->model->stream;
+  int32_t issued = 0;
+  fp_status result = FP_OK;
+  t->timed_ops = 0;
+  auto finish = [&](TaskState st, bool ack) {
+    std::lock_guard<std::mutex> lk(t->mu);
+    t->state = st;
+    if (ack) t->signal.store(0, std::memory_order_release);
+    t->cv.notify_all();
+  };
+  while (t->cursor < total && issued < max_ops) {
+    // Bound how far the host runs ahead of the device: operator i is launched only once
+    // operator i - launch_ahead has completed.
+    if (issued >= t->launch_ahead) {
+      hipError_t e = hipEventSynchronize(t->ring[(issued - t->launch_ahead) % kEventRing]);
+      if (e != hipSuccess) { result = fail(FP_ERR_DEVICE, "event wait: %s", hipGetErrorString(e)); break; }
+    }
+    // Preemption check at the boundary after the previous operator (Section 5.1).
+    const bool boundary = t->cursor == 0 ||
+                          ((t->boundary_mask >> ((t->cursor - 1) % FP_OPS_PER_LAYER)) & 1u);
+    if (boundary && t->signal.load(std::memory_order_acquire)) {
+      hipError_t e = hipStreamSynchronize(s);
+      if (e != hipSuccess) { result = fail(FP_ERR_DEVICE, "drain: %s", hipGetErrorString(e)); break; }
+      if (ops_done) *ops_done = issued;
+      finish(TaskState::Parked, true);
+      return FP_PREEMPTED;
+    }
+    if (t->timing) {
+      if ((int32_t)t->tev.size() < issued + 2) {
+        t->tev.resize((size_t)issued + 2, nullptr);
+      }
+      if (!t->tev[issued]) (void)hipEventCreate(&t->tev[issued]);
+      if (!t->tev[issued + 1]) (void)hipEventCreate(&t->tev[issued + 1]);
+      if (issued == 0) (void)hipEventRecord(t->tev[0], s);
+    }
+    fp_status st = launch_op(t, t->cursor);
+    if (st != FP_OK) { result = st; break; }
+    if (t->timing) { (void)hipEventRecord(t->tev[issued + 1], s); t->timed_ops = issued + 1; }
+    (void)hipEventRecord(t->ring[issued % kEventRing], s);
+    t->cursor++;
+    issued++;
+  }
+  hipError_t e = hipStreamSynchronize(s);
+  if (e != hipSuccess && result >= 0) result = fail(FP_ERR_DEVICE, "stream sync: %s", hipGetErrorString(e));
+  if (ops_done) *ops_done = issued;
+  if (result < 0) {
+    finish(TaskState::Idle, false);
+    return result;
+  }
+  if (t->cursor >= total) {
+    finish(TaskState::Done, true);
+    return FP_DONE;
+  }
+  // More operators remain.  A signal that arrived during the last operators of this call is
+  // honoured here: the device is already quiescent.
+  if (t->signal.load(std::memory_order_acquire)) {
+    finish(TaskState::Parked, true);
+    return FP_PREEMPTED;
+  }
+  finish(TaskState::Idle, false);
+  return FP_OK;
+}
+
+fp_status fp_preempt_signal(fp_prefill* t) {
+  if (!t) return fail(FP_ERR_INVALID, "null task");
+  std::lock_guard<std::mutex> lk(t->mu);
+  switch (t->state) {
+    case TaskState::Running: t->signal.store(1, std::memory_order_release); return FP_OK;
+    case TaskState::Idle: t->state = TaskState::Parked; return FP_PREEMPTED;
+    case TaskState::Done: return FP_DONE;
+    case TaskState::Parked: return fail(FP_ERR_STATE, "task is already parked");
+  }
+  return FP_ERR_STATE;
+}
+
+fp_status fp_preempt_wait(fp_prefill* t) {
+  if (!t) return fail(FP_ERR_INVALID, "null task");
+  std::unique_lock<std::mutex> lk(t->mu);
+  for (;;) {
+    if (t->state == TaskState::Parked) return FP_PREEMPTED;
+    if (t->state == TaskState::Done) return FP_DONE;
+    if (t->state == TaskState::Idle) {
+      if (t->signal.load(std::memory_order_acquire)) {
+        t->signal.store(0, std::memory_order_release);
+        t->state = TaskState::Parked;
+        return FP_PREEMPTED;
+      }
+      return fail(FP_ERR_STATE, "no preemption pending on an idle task");
+    }
+    t->cv.wait(lk);
+  }
+}
+
+fp_status fp_preempt(fp_prefill* t) {
+  fp_status st = fp_preempt_signal(t);
+  if (st != FP_OK) return st;
+  return fp_preempt_wait(t);
+}
+
+fp_status fp_resume(fp_prefill* t) {
+  if (!t) return fail(FP_ERR_INVALID, "null task");
+  std::lock_guard<std::mutex> lk(t->mu);
+  if (t->state != TaskState::Parked) return fail(FP_ERR_STATE, "resume of a task that is not parked");
+  t->state = TaskState::Idle;
+  return FP_OK;
+}
+
+fp_status fp_prefill_cursor(const fp_prefill* t, int32_t* layer, int32_t* op) {
+  if (!t || !layer || !op) return fail(FP_ERR_INVALID, "null argument");
+  *layer = t->cursor / FP_OPS_PER_LAYER;
+  *op = t->cursor % FP_OPS_PER_LAYER;
+  return FP_OK;
+}
+
+fp_status fp_prefill_hidden(const fp_prefill* t, const void** dev_ptr) {
+  if (!t || !dev_ptr) return fail(FP_ERR_INVALID, "null argument");
+  *dev_ptr = t->x;
+  return FP_OK;
+}
+
+fp_status fp_prefill_block_tables(const fp_prefill* t, const int32_t** tables_host, int32_t* max_blocks) {
+  if (!t || !tables_host || !max_blocks) return fail(FP_ERR_INVALID, "null argument");
+  *tables_host = t->tables.data();
+  *max_blocks = t->max_blocks;
+  return FP_OK;
+}
+
+fp_status fp_prefill_kv_gather(const fp_prefill* t, int32_t layer, int32_t seq, void* k_out, void* v_out) {
+  if (!t || !k_out || !v_out) return fail(FP_ERR_INVALID, "null argument");
+  const fp_model* m = t->model;
+  if (layer < 0 || layer >= m->shape.n_layers || seq < 0 || seq >= t->n_seqs)
+    return fail(FP_ERR_INVALID, "layer or sequence out of range");
+  const int len = t->cached[seq] + (t->cu[seq + 1] - t->cu[seq]);
+  fp::launch_kv_gather(m->shape.dtype, m->k_pool, m->v_pool, k_out, v_out, len, m->geo, layer,
+                       t->meta.block_tables + (size_t)seq * t->max_blocks, m->stream);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+  return e == hipSuccess ? FP_OK : fail(FP_ERR_DEVICE, "kv gather: %s", hipGetErrorString(e));
+}
+
+fp_status fp_prefill_op_times(fp_prefill* t, float* ms_out, int32_t n, int32_t* n_out) {
+  if (!t || !ms_out || !n_out || n < 0) return fail(FP_ERR_INVALID, "bad argument");
+  const int32_t cnt = std::min(n, t->timed_ops);
+  for (int32_t i = 0; i < cnt; ++i) {
+    float ms = 0.f;
+    hipError_t e = hipEventElapsedTime(&ms, t->tev[i], t->tev[i + 1]);
+    if (e != hipSuccess) return fail(FP_ERR_DEVICE, "elapsed time: %s", hipGetErrorString(e));
+    ms_out[i] = ms;
+  }
+  *n_out = cnt;
+  return FP_OK;
+}
+
+void fp_prefill_end(fp_prefill* t) {
+  if (!t) return;
+  fp_model* m = t->model;
+  (void)hipStreamSynchronize(m->stream);
+  release_workspace(m, t->ws);
+  if (!t->owned_blocks.empty()) (void)fp_kv_free(m, (int32_t)t->owned_blocks.size(), t->owned_blocks.data());
+  for (auto& ev : t->ring) if (ev) (void)hipEventDestroy(ev);
+  for (auto& ev : t->tev) if (ev) (void)hipEventDestroy(ev);
+  {
+    std::lock_guard<std::mutex> lk(m->mu);
+    m->live_tasks--;
+  }
+  delete t;
+}
+
+fp_status fp_op_gemm(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
+                     int64_t k, int32_t residual, void* hip_stream) {
+  if (!a || !w || !c || m <= 0 || n <= 0 || k <= 0 || (k % 8) || (n % 8) || m > INT32_MAX ||
+      n > INT32_MAX || k > INT32_MAX || (dtype != 0 && dtype != 1))
+    return fail(FP_ERR_INVALID, "fp_op_gemm: bad size, alignment or dtype");
+  fp::launch_gemm(dtype, a, w, c, m, n, k, residual, reinterpret_cast<hipStream_t>(hip_stream));
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? FP_OK : fail(FP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(e));
+}
+
+fp_status fp_op_rmsnorm(int32_t dtype, const void* x_f32, const void* gain, void* out, int64_t t,
+                        int64_t d, float eps, void* hip_stream) {
+  if (!x_f32 || !gain || !out || t <= 0 || d <= 0 || (d % 8) || (dtype != 0 && dtype != 1))
+    return fail(FP_ERR_INVALID, "fp_op_rmsnorm: bad size or dtype");
+  fp::launch_rmsnorm(dtype, (const float*)x_f32, gain, out, t, d, eps, reinterpret_cast<hipStream_t>(hip_stream));
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? FP_OK : fail(FP_ERR_DEVICE, "rmsnorm launch: %s", hipGetErrorString(e));
+}
+
+fp_status fp_op_silu_mul(int32_t dtype, const void* gu, void* out, int64_t t, int64_t f,
+                         void* hip_stream) {
+  if (!gu || !out || t <= 0 || f <= 0 || (f % 8) || (dtype != 0 && dtype != 1))
+    return fail(FP_ERR_INVALID, "fp_op_silu_mul: bad size or dtype");
+  fp::launch_silu_mul(dtype, gu, out, t, f, reinterpret_cast<hipStream_t>(hip_stream));
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? FP_OK : fail(FP_ERR_DEVICE, "silu_mul launch: %s", hipGetErrorString(e));
+}
+
+}  // extern "C"

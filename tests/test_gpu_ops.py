@@ -1,0 +1,93 @@
+"""Single-operator parity: each HIP kernel, called through the C ABI, against the oracle's plain
+definition on the same seeded inputs (sizes span several tiles and ragged tails)."""
+import pytest
+import torch
+
+from oracle import prefill_oracle as O
+from paper_2602_16603_amd import inputs as I
+from tests.util import TOL, max_rel_err
+
+pytestmark = pytest.mark.gpu
+
+DT = {"fp32": (0, torch.float32), "bf16": (1, torch.bfloat16)}
+
+
+def _binding():
+    from paper_2602_16603_amd import binding
+    return binding
+
+
+@pytest.mark.parametrize("name", ["bf16", "fp32"])
+@pytest.mark.parametrize("m,n,k", [
+    (1, 8, 8), (37, 520, 264), (256, 512, 256), (300, 1408, 256), (256, 256, 704),
+    (1000, 256, 704), (513, 776, 1000), (4113, 4096, 512),
+])
+def test_gemm_matches_definition(name, m, n, k):
+    B = _binding()
+    code, td = DT[name]
+    print(f"gemm {name} m={m} n={n} k={k}", flush=True)
+    a = I.normal_tensor((m, k), 1.0, 11, td, "cuda")
+    w = I.normal_tensor((n, k), 0.05, 12, td, "cuda")
+    c = torch.full((m, n), float("nan"), dtype=td, device="cuda")
+    torch.cuda.synchronize()
+    B.fp_op_gemm(code, a.data_ptr(), w.data_ptr(), c.data_ptr(), m, n, k, False)
+    torch.cuda.synchronize()
+    ref = O.linear(a.cpu(), w.cpu())
+    assert max_rel_err(c, ref) <= TOL[name]
+
+
+@pytest.mark.parametrize("name", ["bf16", "fp32"])
+@pytest.mark.parametrize("m,n,k", [(300, 264, 520), (4113, 4096, 256)])
+def test_gemm_residual_accumulates_into_fp32(name, m, n, k):
+    B = _binding()
+    code, td = DT[name]
+    print(f"gemm-residual {name} m={m} n={n} k={k}", flush=True)
+    a = I.normal_tensor((m, k), 1.0, 13, td, "cuda")
+    w = I.normal_tensor((n, k), 0.05, 14, td, "cuda")
+    x = I.normal_tensor((m, n), 1.0, 15, torch.float32, "cuda")
+    x0 = x.clone()
+    torch.cuda.synchronize()
+    B.fp_op_gemm(code, a.data_ptr(), w.data_ptr(), x.data_ptr(), m, n, k, True)
+    torch.cuda.synchronize()
+    ref = x0.cpu().double() + O.linear(a.cpu(), w.cpu())
+    assert max_rel_err(x, ref) <= TOL[name]
+
+
+@pytest.mark.parametrize("name", ["bf16", "fp32"])
+@pytest.mark.parametrize("t,d", [(1, 256), (77, 4096), (5, 5120), (3, 8200), (2, 20000)])
+def test_rmsnorm_matches_definition(name, t, d):
+    B = _binding()
+    code, td = DT[name]
+    x = I.normal_tensor((t, d), 3.0, 16, torch.float32, "cuda")
+    g = (1.0 + I.normal_tensor((d,), 0.1, 17, torch.float32, "cuda")).to(td)
+    out = torch.empty((t, d), dtype=td, device="cuda")
+    torch.cuda.synchronize()
+    B.fp_op_rmsnorm(code, x.data_ptr(), g.data_ptr(), out.data_ptr(), t, d, 1e-5)
+    torch.cuda.synchronize()
+    ref = O.rmsnorm(x.cpu(), g.cpu(), 1e-5)
+    assert max_rel_err(out, ref) <= TOL[name]
+
+
+@pytest.mark.parametrize("name", ["bf16", "fp32"])
+@pytest.mark.parametrize("t,f", [(1, 8), (33, 704), (7, 14336)])
+def test_silu_mul_matches_definition(name, t, f):
+    B = _binding()
+    code, td = DT[name]
+    gu = I.normal_tensor((t, 2 * f), 2.0, 18, td, "cuda")
+    out = torch.empty((t, f), dtype=td, device="cuda")
+    torch.cuda.synchronize()
+    B.fp_op_silu_mul(code, gu.data_ptr(), out.data_ptr(), t, f)
+    torch.cuda.synchronize()
+    ref = O.silu_mul(gu.cpu())
+    assert max_rel_err(out, ref) <= TOL[name]
+
+
+def test_bad_sizes_are_rejected_not_launched():
+    B = _binding()
+    a = torch.zeros(64, device="cuda")
+    with pytest.raises(B.FlowPrefillError):
+        B.fp_op_gemm(1, a.data_ptr(), a.data_ptr(), a.data_ptr(), 4, 8, 12, False)   # K % 8
+    with pytest.raises(B.FlowPrefillError):
+        B.fp_op_gemm(1, a.data_ptr(), a.data_ptr(), a.data_ptr(), 0, 8, 8, False)
+    with pytest.raises(B.FlowPrefillError):
+        B.fp_op_rmsnorm(1, a.data_ptr(), a.data_ptr(), a.data_ptr(), 1, 12, 1e-5)
