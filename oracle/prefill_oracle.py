@@ -151,6 +151,8 @@ def causal_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
     key_pos = torch.arange(m).reshape(1, m)
     visible = key_pos <= q_positions.reshape(n, 1)                                # [n, m]
     out = torch.empty((n, hq, dim), dtype=F64)
+    if n == 0:                       # an empty sequence in a packed batch has no rows to fill
+        return out
     for h in range(hq):
         g = h // group
         scores = torch.matmul(q[:, h, :], k[:, g, :].transpose(0, 1)) * scale    # [n, m]

@@ -32,20 +32,22 @@ __device__ __forceinline__ void tile_of_workgroup(int wg, int tiles_m, int tiles
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16 MFMA GEMM.  256 threads = 4 waves in a 2x2 grid; each wave owns a (BM/2)x(BN/2) block of
-// 32x32 MFMA accumulators.  K is consumed 64 at a time.  LDS rows hold 64 bf16 = eight 16-byte
-// chunks; chunk c of row r is stored at chunk position c ^ (r & 7) so that the eight lanes of a
-// ds_read_b128 phase hit distinct banks.
+// bf16 MFMA GEMM.  WGM x WGN waves; each wave owns a (BM/WGM)x(BN/WGN) block of 32x32 MFMA
+// accumulators.  K is consumed 64 at a time.  LDS rows hold 64 bf16 = eight 16-byte chunks.  The
+// gfx950 LDS has 64 four-byte banks (256 B per clock for reads) and serves a ds_read_b128 sixteen
+// lanes at a time, so two consecutive 128-byte rows fill one bank period: chunk c of row r is
+// stored at chunk position c ^ ((r >> 1) & 7), which makes the 16 rows a read phase touches land
+// on 16 distinct 16-byte bank groups (measured: conflict-free, against 2-way with key r & 7).
 // ------------------------------------------------------------------------------------------
 constexpr int kBK = 64;
 
-template <int ROWS>
+template <int ROWS, int NT>
 __device__ __forceinline__ void load_tile_global(const bf16* __restrict__ src, int64_t ld,
                                                  int row0, int row_max, int k0, int K, int tid,
-                                                 u32x4 (&regs)[ROWS / 32]) {
+                                                 u32x4 (&regs)[ROWS * 8 / NT]) {
 #pragma unroll
-  for (int i = 0; i < ROWS / 32; ++i) {
-    const int c = tid + i * 256;
+  for (int i = 0; i < ROWS * 8 / NT; ++i) {
+    const int c = tid + i * NT;
     const int row = c >> 3, ch = c & 7;
     const int grow = min(row0 + row, row_max);
     const int k = k0 + ch * 8;
@@ -56,29 +58,30 @@ __device__ __forceinline__ void load_tile_global(const bf16* __restrict__ src, i
   }
 }
 
-template <int ROWS>
-__device__ __forceinline__ void store_tile_lds(bf16* dst, int tid, const u32x4 (&regs)[ROWS / 32]) {
+template <int ROWS, int NT>
+__device__ __forceinline__ void store_tile_lds(bf16* dst, int tid, const u32x4 (&regs)[ROWS * 8 / NT]) {
 #pragma unroll
-  for (int i = 0; i < ROWS / 32; ++i) {
-    const int c = tid + i * 256;
+  for (int i = 0; i < ROWS * 8 / NT; ++i) {
+    const int c = tid + i * NT;
     const int row = c >> 3, ch = c & 7;
-    *reinterpret_cast<u32x4*>(dst + row * kBK + ((ch ^ (row & 7)) << 3)) = regs[i];
+    *reinterpret_cast<u32x4*>(dst + row * kBK + ((ch ^ ((row >> 1) & 7)) << 3)) = regs[i];
   }
 }
 
-template <int BM, int BN, bool RESID>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restrict__ A,
+template <int BM, int BN, int WGM, int WGN, bool RESID>
+__global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16* __restrict__ A,
                                                            const bf16* __restrict__ W,
                                                            void* __restrict__ Cout, int M, int N,
                                                            int K, int tiles_m, int tiles_n) {
-  constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* sA = reinterpret_cast<bf16*>(smem_raw);            // [2][BM*64]
   bf16* sB = sA + 2 * BM * kBK;                            // [2][BN*64]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
   int tile_m, tile_n;
   tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -91,20 +94,20 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  u32x4 ra[BM / 32], rb[BN / 32];
+  u32x4 ra[BM * 8 / NT], rb[BN * 8 / NT];
   const int kt_count = (K + kBK - 1) / kBK;
-  load_tile_global<BM>(A, K, m0, M - 1, 0, K, tid, ra);
-  load_tile_global<BN>(W, K, n0, N - 1, 0, K, tid, rb);
-  store_tile_lds<BM>(sA, tid, ra);
-  store_tile_lds<BN>(sB, tid, rb);
+  load_tile_global<BM, NT>(A, K, m0, M - 1, 0, K, tid, ra);
+  load_tile_global<BN, NT>(W, K, n0, N - 1, 0, K, tid, rb);
+  store_tile_lds<BM, NT>(sA, tid, ra);
+  store_tile_lds<BN, NT>(sB, tid, rb);
   __syncthreads();
 
   const int frag_row = lane & 31, frag_half = lane >> 5;
   for (int kt = 0; kt < kt_count; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < kt_count) {
-      load_tile_global<BM>(A, K, m0, M - 1, (kt + 1) * kBK, K, tid, ra);
-      load_tile_global<BN>(W, K, n0, N - 1, (kt + 1) * kBK, K, tid, rb);
+      load_tile_global<BM, NT>(A, K, m0, M - 1, (kt + 1) * kBK, K, tid, ra);
+      load_tile_global<BN, NT>(W, K, n0, N - 1, (kt + 1) * kBK, K, tid, rb);
     }
     const bf16* cA = sA + cur * BM * kBK;
     const bf16* cB = sB + cur * BN * kBK;
@@ -115,12 +118,12 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int row = wm * WTM + i * 32 + frag_row;
-        fa[i] = *reinterpret_cast<const bf16x8*>(cA + row * kBK + ((ch ^ (row & 7)) << 3));
+        fa[i] = *reinterpret_cast<const bf16x8*>(cA + row * kBK + ((ch ^ ((row >> 1) & 7)) << 3));
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int row = wn * WTN + j * 32 + frag_row;
-        fb[j] = *reinterpret_cast<const bf16x8*>(cB + row * kBK + ((ch ^ (row & 7)) << 3));
+        fb[j] = *reinterpret_cast<const bf16x8*>(cB + row * kBK + ((ch ^ ((row >> 1) & 7)) << 3));
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -129,8 +132,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < kt_count) {
-      store_tile_lds<BM>(sA + (cur ^ 1) * BM * kBK, tid, ra);
-      store_tile_lds<BN>(sB + (cur ^ 1) * BN * kBK, tid, rb);
+      store_tile_lds<BM, NT>(sA + (cur ^ 1) * BM * kBK, tid, ra);
+      store_tile_lds<BN, NT>(sB + (cur ^ 1) * BN * kBK, tid, rb);
     }
     __syncthreads();
   }
@@ -158,18 +161,225 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const bf16* __restric
   }
 }
 
-template <int BM, int BN, bool RESID>
+// ------------------------------------------------------------------------------------------
+// Ping-pong bf16 MFMA GEMM (the fast path; K % 64 == 0).
+//
+// 256x256 output tile, K consumed 64 at a time, 512 threads = 8 waves.  The hardware places the
+// waves of a workgroup round-robin on the CU's four SIMDs, so waves w and w+4 share a SIMD.  The
+// two wave groups {0..3} and {4..7} run the same loop half an iteration apart: while one group
+// issues its 32 MFMAs from registers ("compute phase"), the other pulls its MFMA operands for
+// the same k-tile out of LDS ("memory phase"); one s_barrier ends every phase.  The matrix pipe
+// of each SIMD therefore always has a wave with all operands resident, independent of how the
+// compiler schedules inside a phase.
+//
+// Global -> LDS goes through the DMA path (buffer_load_dwordx4 ... lds: no VGPR staging, no
+// ds_write).  A DMA instruction writes lane i's 16 bytes at base + 16*i, i.e. one wave fills
+// eight consecutive 128-byte LDS rows; the LDS swizzle is obtained by permuting which 16-byte
+// global chunk each lane fetches.  Two LDS stages (A and B, 32 KB each per stage).  Group 1
+// does all the loading: during its compute phase of k-tile t -- the first moment at which both
+// groups have finished reading stage t%2 -- it refills that stage with k-tile t+2, one DMA
+// instruction per two MFMAs, and awaits it at the end of its next memory phase, i.e. before the
+// barrier that lets group 0 start reading k-tile t+2.  Stages are separate __shared__ arrays so
+// that the compiler can tell that DMA in flight to one stage does not alias LDS reads of the
+// other (otherwise it would serialise them with vmcnt(0)).  Operand panels are addressed through
+// raw buffer descriptors sized to the valid rows, so row tails of A and W read as zero.
+// ------------------------------------------------------------------------------------------
+constexpr int kWaitVm0 = 0x0F70;   // s_waitcnt vmcnt(0)           (expcnt/lgkmcnt untouched)
+constexpr int kWaitLgkm0 = 0xC07F; // s_waitcnt lgkmcnt(0)         (vmcnt/expcnt untouched)
+
+struct PpFrags {
+  bf16x8 a[4][4];   // [32-row block][k-step]
+  bf16x8 b[2][4];
+};
+
+// Raw buffer descriptor over `bytes` bytes at `base` (stride 0, 32-bit offsets, reads past the
+// end return zero -- which is how row tails of A and W are zero-filled).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t pp_panel_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ void pp_issue_tile(__amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rw,
+                                              int kbyte, const uint32_t (&voff)[8], bf16* sA, bf16* sB,
+                                              int w4) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int base_row = (w4 * 8 + j) * 8;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        ra, (__attribute__((address_space(3))) void*)(sA + base_row * kBK), 16, voff[j], kbyte, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        rw, (__attribute__((address_space(3))) void*)(sB + base_row * kBK), 16, voff[j], kbyte, 0, 0);
+  }
+}
+
+__device__ __forceinline__ void pp_read_frags(const bf16* sA, const bf16* sB, int a_row0,
+                                              int b_row0, int key, int half, PpFrags& f) {
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const int pch = ((kk * 2 + half) ^ key) << 3;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      f.a[i][kk] = *reinterpret_cast<const bf16x8*>(sA + (a_row0 + i * 32) * kBK + pch);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      f.b[j][kk] = *reinterpret_cast<const bf16x8*>(sB + (b_row0 + j * 32) * kBK + pch);
+  }
+}
+
+// Compute phase: the 32 MFMAs of one k-tile.  In the loading group (`load` set, wave-uniform)
+// the 16 DMA instructions of one whole k-tile (8 for A, 8 for W per wave of the group) are
+// slotted in one per two MFMAs, so the address unit (16 clocks per dwordx4 instruction) never
+// backs up into the wave's in-order issue.  The branches are scalar and keep MFMAs and loads in
+// source order without further scheduling directives.
+__device__ __forceinline__ void pp_mfma_and_loads(const PpFrags& f, f32x16 (&acc)[4][2], bool load,
+                                                  __amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rw,
+                                                  int kbyte, const uint32_t (&voff)[8], bf16* sA,
+                                                  bf16* sB, int w4) {
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i][kk], f.b[j][kk], acc[i][j], 0, 0, 0);
+      if (load) {
+        const int slot = kk * 4 + i;            // 0..15: slots 0..7 load A rows, 8..15 load W rows
+        const int base_row = (w4 * 8 + (slot & 7)) * 8;
+        if (slot < 8)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(
+              ra, (__attribute__((address_space(3))) void*)(sA + base_row * kBK), 16, voff[slot & 7], kbyte, 0, 0);
+        else
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(
+              rw, (__attribute__((address_space(3))) void*)(sB + base_row * kBK), 16, voff[slot & 7], kbyte, 0, 0);
+      }
+    }
+}
+
+__device__ __forceinline__ void pp_barrier() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+template <bool RESID>
+__global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restrict__ A,
+                                                           const bf16* __restrict__ W,
+                                                           void* __restrict__ Cout, int M, int N,
+                                                           int K, int tiles_m, int tiles_n) {
+  constexpr int BM = 256, BN = 256;
+  __shared__ __attribute__((aligned(1024))) bf16 sA0[BM * kBK];
+  __shared__ __attribute__((aligned(1024))) bf16 sA1[BM * kBK];
+  __shared__ __attribute__((aligned(1024))) bf16 sB0[BN * kBK];
+  __shared__ __attribute__((aligned(1024))) bf16 sB1[BN * kBK];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int group = wave >> 2;
+  const int wm = wave & 1, wn = wave >> 1;           // 2 x 4 waves, wave tile 128 x 64
+  int tile_m, tile_n;
+  tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  // Per-lane byte offsets of the DMA sources inside the tile's row panel (the same for the A
+  // and the W panel: both have K as row stride).  The four waves of group 1 load whole k-tiles:
+  // wave w4 covers rows [64*w4, 64*w4+64) of each operand, 8 rows per instruction.
+  const int w4 = wave & 3;
+  uint32_t voff[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int row = (w4 * 8 + j) * 8 + (lane >> 3);
+    const int ch = (lane & 7) ^ ((row >> 1) & 7);
+    voff[j] = (uint32_t)((row * K + ch * 8) * 2);
+  }
+  const __amdgpu_buffer_rsrc_t rsrc_a =
+      pp_panel_rsrc(A + (int64_t)m0 * K, (uint32_t)(min(BM, M - m0) * K * 2));
+  const __amdgpu_buffer_rsrc_t rsrc_w =
+      pp_panel_rsrc(W + (int64_t)n0 * K, (uint32_t)(min(BN, N - n0) * K * 2));
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int kt_count = K / kBK;
+  if (group == 1) {
+    pp_issue_tile(rsrc_a, rsrc_w, 0, voff, sA0, sB0, w4);
+    if (kt_count > 1) pp_issue_tile(rsrc_a, rsrc_w, kBK * 2, voff, sA1, sB1, w4);
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+  }
+  pp_barrier();
+
+  const int frag_row = lane & 31, half = lane >> 5;
+  const int key = (lane >> 1) & 7;
+  const int a_row0 = wm * 128 + frag_row, b_row0 = wn * 64 + frag_row;
+  PpFrags f;
+
+  // One iteration = memory phase + compute phase of k-tile t on the given stage.
+  auto iteration = [&](int t, bf16* sA, bf16* sB, bf16* sA_other, bf16* sB_other) {
+    // -- memory phase --
+    pp_read_frags(sA, sB, a_row0, b_row0, key, half, f);
+    if (group == 1) __builtin_amdgcn_s_waitcnt(kWaitVm0);   // k-tile t+1, issued one iteration ago
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    pp_barrier();
+    // -- compute phase --
+    // Both groups have finished reading this stage (group 0 one phase ago, group 1 just now):
+    // group 1 refills it with k-tile t+2 while it computes.
+    pp_mfma_and_loads(f, acc, group == 1 && t + 2 < kt_count, rsrc_a, rsrc_w, (t + 2) * kBK * 2,
+                      voff, sA, sB, w4);
+    pp_barrier();
+  };
+
+  if (group == 1) pp_barrier();                          // run half an iteration behind group 0
+  for (int t = 0; t < kt_count; t += 2) {
+    iteration(t, sA0, sB0, sA1, sB1);
+    if (t + 1 < kt_count) iteration(t + 1, sA1, sB1, sA0, sB0);
+  }
+  if (group == 0) pp_barrier();
+
+  // Epilogue (accumulator layout as in the kernel above).
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = n0 + wn * 64 + j * 32 + frag_row;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (m < M && n < N) {
+          if (RESID) {
+            float* c = reinterpret_cast<float*>(Cout) + (int64_t)m * N + n;
+            *c = *c + acc[i][j][r];
+          } else {
+            reinterpret_cast<bf16*>(Cout)[(int64_t)m * N + n] = static_cast<bf16>(acc[i][j][r]);
+          }
+        }
+      }
+    }
+  }
+}
+
+template <bool RESID>
+static void launch_bf16_pp(const bf16* a, const bf16* w, void* c, int m, int n, int k, hipStream_t s) {
+  const int tiles_m = (m + 255) / 256, tiles_n = (n + 255) / 256;
+  gemm_bf16_pp_kernel<RESID><<<dim3((unsigned)(tiles_m * tiles_n)), 512, 0, s>>>(a, w, c, m, n, k,
+                                                                               tiles_m, tiles_n);
+}
+
+template <int BM, int BN, int WGM, int WGN, bool RESID>
 static void launch_bf16_cfg(const bf16* a, const bf16* w, void* c, int m, int n, int k,
                             hipStream_t s) {
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
   const size_t smem = (size_t)2 * (BM + BN) * kBK * sizeof(bf16);
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, RESID>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, WGM, WGN, RESID>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
-  gemm_bf16_kernel<BM, BN, RESID><<<dim3((unsigned)(tiles_m * tiles_n)), 256, smem, s>>>(
+  gemm_bf16_kernel<BM, BN, WGM, WGN, RESID><<<dim3((unsigned)(tiles_m * tiles_n)), WGM * WGN * 64, smem, s>>>(
       a, w, c, m, n, k, tiles_m, tiles_n);
 }
 
@@ -238,14 +448,15 @@ void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, in
   }
   const bf16* pa = (const bf16*)a;
   const bf16* pw = (const bf16*)w;
-  // 256x256 tiles when they fill the chip (>= one tile per CU); else 128x128 tiles.
+  // Large problems with K a multiple of 64: the ping-pong DMA kernel on 256x256 tiles.  Small
+  // or odd-K problems: the register-staged kernel on 128x128 tiles.
   const int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
-  if (big_tiles >= 256) {
-    if (residual) launch_bf16_cfg<256, 256, true>(pa, pw, c, (int)m, (int)n, (int)k, s);
-    else launch_bf16_cfg<256, 256, false>(pa, pw, c, (int)m, (int)n, (int)k, s);
+  if (k % kBK == 0 && big_tiles >= 192) {
+    if (residual) launch_bf16_pp<true>(pa, pw, c, (int)m, (int)n, (int)k, s);
+    else launch_bf16_pp<false>(pa, pw, c, (int)m, (int)n, (int)k, s);
   } else {
-    if (residual) launch_bf16_cfg<128, 128, true>(pa, pw, c, (int)m, (int)n, (int)k, s);
-    else launch_bf16_cfg<128, 128, false>(pa, pw, c, (int)m, (int)n, (int)k, s);
+    if (residual) launch_bf16_cfg<128, 128, 2, 2, true>(pa, pw, c, (int)m, (int)n, (int)k, s);
+    else launch_bf16_cfg<128, 128, 2, 2, false>(pa, pw, c, (int)m, (int)n, (int)k, s);
   }
 }
 
