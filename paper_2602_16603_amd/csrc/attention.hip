@@ -10,41 +10,63 @@ namespace fp {
 // ------------------------------------------------------------------------------------------
 // bf16 kernel.
 //
-// One workgroup = NW waves = one (sequence, query tile of NW*32*NQ rows, query head).  Keys are
-// consumed 64 at a time (four 16-token cache blocks), staged in LDS, double-buffered.
+// One workgroup = 8 waves = one (sequence, query tile of 256 rows, query head); each wave owns
+// 32 query rows.  Two waves share a SIMD, so one wave's softmax arithmetic (VALU, exp) overlaps
+// the other's MFMAs.  Keys are consumed 64 at a time (four 16-token cache blocks), staged in LDS,
+// double-buffered.
 //
 // The score tile is computed TRANSPOSED, S^T = K Q^T: the MFMA accumulator layout then gives
 // each lane one query column and 16 key rows per 32-key block, so the row maximum and row sum of
-// the softmax are in-lane reductions plus one exchange with lane^32, the rescale factor is a
-// per-lane scalar, and exp(S^T) converted to bf16 is already laid out as the B operand of the
-// second MFMA, O^T += V^T P^T -- no LDS round trip for P.
+// the softmax are in-lane reductions plus one exchange with lane^32 (v_permlane32_swap), the
+// rescale factor is a per-lane scalar, and exp(S^T) converted to bf16 is already laid out as the
+// B operand of the second MFMA, O^T += V^T P^T -- no LDS round trip for P.
 //
 // Accumulator row i = 8a + 4h + b (a = reg/4, h = lane/32, b = reg%4) of a 32-row block, while
 // the B operand wants k = 8h + e.  Loading key pi(i) into MFMA row i, pi = swap of bits 2 and 3,
 // makes registers 8*a1 .. 8*a1+7 of a lane hold the 8 consecutive keys 16*a1 + 8h + (0..7): one
 // B operand per 16-key chunk, matching V^T read in natural key order.
 //
-// LDS layouts (16-byte chunks):
-//   K tile [64 keys][D]      chunk c of key row r stored at c ^ ((r&3) | ((r&8)>>1))
-//   V tile [4 blocks][D][16] the two 16-byte halves of channel row d swapped when d & 4
-// Both make the 8 lanes of a ds_read_b128 phase hit distinct banks.
+// The running maximum is applied lazily: the exponent reference m_use is only moved (and O, l
+// rescaled) when some row's maximum has grown by more than 2^8 since the reference was set, so
+// exp2 arguments stay <= 8 and almost every tile skips the D/32*16 rescale multiplies.
+//
+// LDS layouts (16-byte chunks; the LDS has 64 banks and serves b128 reads 16 lanes at a time):
+//   K tile [64 keys][D]      chunk c of key row r stored at c ^ key(r), key chosen so that the
+//                            16 rows one read phase touches fall on 16 distinct bank groups
+//   V tile [4 blocks][D][16] the two 16-byte halves of channel row d swapped when d & 8
 // ------------------------------------------------------------------------------------------
 constexpr int kKT = 64;   // keys per tile
 
-template <int D, int NQ, int NW>
-__global__ __launch_bounds__(NW * 64, 1) void attn_bf16_kernel(
+__device__ __forceinline__ float xhalf_max(float v) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xhalf_sum(float v) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// LDS swizzle key of the K tile as a function of the MFMA row (= lane & 31) that reads it.
+template <int D> __device__ __forceinline__ int k_key_of_lane(int lq) {
+  return D == 128 ? (lq & 15) : ((lq >> 1) & 7);
+}
+__device__ __forceinline__ int pi_swap23(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
+
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
     const bf16* __restrict__ qkv, const bf16* __restrict__ k_pool, const bf16* __restrict__ v_pool,
     bf16* __restrict__ o, int n_q_heads, int n_kv_heads, int64_t kv_num_blocks, int layer,
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ cached_lens,
     const int32_t* __restrict__ block_tables, int max_blocks,
     const int32_t* __restrict__ attn_items, float scale_log2) {
-  static_assert(NW * 64 == 256, "tile loaders assume 256 threads");
-  constexpr int BQW = NW * 32 * NQ;
+  constexpr int NT = NW * 64;
+  constexpr int BQW = NW * 32;
   constexpr int CPR = D / 8;                 // 16-byte chunks per key row
   constexpr int CH = kKvBlock * CPR;         // chunks per 16-token block
-  constexpr int PASSES = 4 * CH / 256;       // per-thread chunks per tile (K and V each)
+  constexpr int PASSES = 4 * CH / NT;        // per-thread chunks per tile (K and V each)
   constexpr int DB = D / 32;                 // 32-channel blocks of the output
   constexpr int KK = D / 16;                 // MFMA k-steps of the score contraction
+  static_assert(PASSES >= 1 && 4 * CH % NT == 0, "tile loaders need 4*CH to be a multiple of NT");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* sK = reinterpret_cast<bf16*>(smem_raw);   // [2][64*D]
@@ -66,7 +88,7 @@ __global__ __launch_bounds__(NW * 64, 1) void attn_bf16_kernel(
   const int cached = cached_lens[s];
   const int total = cached + n_new;
   const int q_row0 = qt * BQW;
-  const int wq0 = q_row0 + wave * 32 * NQ;
+  const int wq0 = q_row0 + wave * 32;
   const int kv_len = cached + min(n_new, q_row0 + BQW);
   const int n_tiles = (kv_len + kKT - 1) / kKT;
   const int64_t width = (int64_t)(n_q_heads + 2 * n_kv_heads) * D;
@@ -74,31 +96,27 @@ __global__ __launch_bounds__(NW * 64, 1) void attn_bf16_kernel(
   const int64_t pool_layer = (int64_t)layer * kv_num_blocks;
 
   // ---- query fragments (B operand of S^T = K Q^T), resident for the whole kernel ----
-  bf16x8 qf[NQ][KK];
-#pragma unroll
-  for (int nq = 0; nq < NQ; ++nq) {
-    const int row = min(wq0 + nq * 32 + lq, n_new - 1);
+  bf16x8 qf[KK];
+  {
+    const int row = min(wq0 + lq, n_new - 1);
     const bf16* src = qkv + (int64_t)(seq_lo + row) * width + head * D + lh * 8;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) qf[nq][kk] = *reinterpret_cast<const bf16x8*>(src + kk * 16);
+    for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(src + kk * 16);
   }
 
-  f32x16 oacc[DB][NQ];
+  f32x16 oacc[DB];
 #pragma unroll
   for (int i = 0; i < DB; ++i)
 #pragma unroll
-    for (int j = 0; j < NQ; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[i][j][r] = 0.f;
-  float m_run[NQ], l_run[NQ];
-#pragma unroll
-  for (int j = 0; j < NQ; ++j) { m_run[j] = -INFINITY; l_run[j] = 0.f; }
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+  float m_use = -INFINITY;      // exponent reference (raw score units)
+  float l_run = 0.f;            // this lane's half of the row sum
 
   u32x4 rk[PASSES], rv[PASSES];
   auto load_tile = [&](int tile) {
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
-      const int flat = tid + i * 256;
+      const int flat = tid + i * NT;
       const int c = flat / CH, chunk = flat % CH;
       const int lb = tile * 4 + c;
       if (lb * kKvBlock < total) {
@@ -117,28 +135,28 @@ __global__ __launch_bounds__(NW * 64, 1) void attn_bf16_kernel(
     bf16* dV = sV + buf * kKT * D;
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
-      const int flat = tid + i * 256;
+      const int flat = tid + i * NT;
       const int c = flat / CH, chunk = flat % CH;
       const int key = chunk / CPR, dch = chunk % CPR;
       const int row = c * kKvBlock + key;
-      const int swz = (row & 3) | ((row & 8) >> 1);
+      const int swz = k_key_of_lane<D>(pi_swap23(row & 31));
       *reinterpret_cast<u32x4*>(dK + row * D + ((dch ^ swz) << 3)) = rk[i];
       const int d = chunk >> 1, half = chunk & 1;
-      const int phys = d * 2 + (half ^ ((d >> 2) & 1));
+      const int phys = d * 2 + (half ^ ((d >> 3) & 1));
       *reinterpret_cast<u32x4*>(dV + c * (D * kKvBlock) + (phys << 3)) = rv[i];
     }
   };
 
-  if (n_tiles > 0) {
-    load_tile(0);
-    store_tile(0);
-  }
+  load_tile(0);
+  store_tile(0);
   __syncthreads();
 
-  const int wave_q_min = cached + wq0;                    // smallest query position of the wave
-  const int wave_q_max = cached + wq0 + 32 * NQ - 1;      // largest
-  const int pi_row = (lq & ~12) | ((lq & 4) << 1) | ((lq & 8) >> 1);
-  const int k_swz = lq & 7;
+  const int wave_q_min = cached + wq0;               // smallest query position of the wave
+  const int wave_q_max = cached + wq0 + 31;          // largest
+  const int qpos = cached + wq0 + lq;
+  const int pi_row = pi_swap23(lq);
+  const int k_swz = k_key_of_lane<D>(lq);
+  const float lazy_gap = 8.0f / scale_log2;          // 2^8 of head-room, in raw score units
 
   for (int t = 0; t < n_tiles; ++t) {
     const int cur = t & 1;
@@ -148,80 +166,69 @@ __global__ __launch_bounds__(NW * 64, 1) void attn_bf16_kernel(
       const bf16* cK = sK + cur * kKT * D;
       const bf16* cV = sV + cur * kKT * D;
       // ---- S^T = K Q^T ----
-      f32x16 sacc[2][NQ];
+      f32x16 sacc[2];
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
 #pragma unroll
-        for (int j = 0; j < NQ; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[rb][j][r] = 0.f;
+        for (int r = 0; r < 16; ++r) sacc[rb][r] = 0.f;
         const bf16* krow = cK + (rb * 32 + pi_row) * D;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
           const int dch = kk * 2 + lh;
           bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + ((dch ^ k_swz) << 3));
-#pragma unroll
-          for (int j = 0; j < NQ; ++j)
-            sacc[rb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[j][kk], sacc[rb][j], 0, 0, 0);
+          sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[rb], 0, 0, 0);
         }
       }
-      // ---- online softmax, per query column ----
-      const bool need_mask = key0 + kKT - 1 > wave_q_min;
-      bf16x8 pf[NQ][4];
-#pragma unroll
-      for (int j = 0; j < NQ; ++j) {
-        const int qpos = cached + wq0 + j * 32 + lq;
-        float mx = -INFINITY;
+      // ---- online softmax for this lane's query column ----
+      if (key0 + kKT - 1 > wave_q_min) {              // tile straddles the diagonal: mask
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            float x = sacc[rb][j][r] * scale_log2;
-            if (need_mask) {
-              const int key = key0 + rb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
-              x = key <= qpos ? x : -INFINITY;
-            }
-            sacc[rb][j][r] = x;
-            mx = fmaxf(mx, x);
+            const int key = key0 + rb * 32 + 16 * (r >> 3) + 8 * lh + (r & 7);
+            sacc[rb][r] = key <= qpos ? sacc[rb][r] : -INFINITY;
           }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run[j], mx);
-        // m_new is finite from the first tile on: key 0 is visible to every query.
-        const float alpha = __builtin_amdgcn_exp2f(m_run[j] - m_new);
-        m_run[j] = m_new;
-        float psum = 0.f;
+      }
+      float mx = -INFINITY;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+      for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(sacc[rb][j][r] - m_new);
-            sacc[rb][j][r] = p;
-            psum += p;
-          }
-        l_run[j] = l_run[j] * alpha + psum;
+        for (int r = 0; r < 16; r += 2) mx = fmaxf(mx, fmaxf(sacc[rb][r], sacc[rb][r + 1]));
+      mx = xhalf_max(mx);
+      // Key 0 is visible to every query, so mx is finite from the first tile on.
+      if (__any(mx > m_use + lazy_gap)) {
+        const float m_new = fmaxf(m_use, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_use - m_new) * scale_log2);
+        m_use = m_new;
+        l_run *= alpha;
 #pragma unroll
         for (int i = 0; i < DB; ++i)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[i][j][r] *= alpha;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          f32x8 pv;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) pv[e] = sacc[c >> 1][j][8 * (c & 1) + e];
-          pf[j][c] = __builtin_convertvector(pv, bf16x8);
-        }
+          for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
       }
+      const float mc = m_use * scale_log2;
+      float psum = 0.f;
+      bf16x8 pf[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        f32x8 pv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          pv[e] = __builtin_amdgcn_exp2f(fmaf(sacc[c >> 1][8 * (c & 1) + e], scale_log2, -mc));
+          psum += pv[e];
+        }
+        pf[c] = __builtin_convertvector(pv, bf16x8);
+      }
+      l_run += psum;
       // ---- O^T += V^T P^T ----
 #pragma unroll
       for (int i = 0; i < DB; ++i) {
         const int d = i * 32 + lq;
-        const int phys = d * 2 + (lh ^ ((d >> 2) & 1));
+        const int phys = d * 2 + (lh ^ ((d >> 3) & 1));
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           bf16x8 vf = *reinterpret_cast<const bf16x8*>(cV + c * (D * kKvBlock) + (phys << 3));
-#pragma unroll
-          for (int j = 0; j < NQ; ++j)
-            oacc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[j][c], oacc[i][j], 0, 0, 0);
+          oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[c], oacc[i], 0, 0, 0);
         }
       }
     }
@@ -230,12 +237,10 @@ __global__ __launch_bounds__(NW * 64, 1) void attn_bf16_kernel(
   }
 
   // ---- normalise, stage through LDS, store rows with 16-byte accesses ----
-  bf16* stage = reinterpret_cast<bf16*>(smem_raw) + wave * (32 * NQ * D);
-#pragma unroll
-  for (int j = 0; j < NQ; ++j) {
-    const float l_tot = l_run[j] + __shfl_xor(l_run[j], 32, 64);
+  bf16* stage = reinterpret_cast<bf16*>(smem_raw) + wave * (32 * D);
+  {
+    const float l_tot = xhalf_sum(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    const int row = j * 32 + lq;
 #pragma unroll
     for (int i = 0; i < DB; ++i)
 #pragma unroll
@@ -243,15 +248,15 @@ __global__ __launch_bounds__(NW * 64, 1) void attn_bf16_kernel(
         const int d = i * 32 + 8 * a + 4 * lh;
         bf16x4 v4;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) v4[b] = static_cast<bf16>(oacc[i][j][4 * a + b] * inv);
+        for (int b = 0; b < 4; ++b) v4[b] = static_cast<bf16>(oacc[i][4 * a + b] * inv);
         const int dch = d >> 3;
-        *reinterpret_cast<bf16x4*>(stage + row * D + ((dch ^ (row & 7)) << 3) + (d & 7)) = v4;
+        *reinterpret_cast<bf16x4*>(stage + lq * D + ((dch ^ (lq & 7)) << 3) + (d & 7)) = v4;
       }
   }
   __syncthreads();
   const int64_t o_width = (int64_t)n_q_heads * D;
 #pragma unroll
-  for (int i = 0; i < 32 * NQ * CPR / 64; ++i) {
+  for (int i = 0; i < 32 * CPR / 64; ++i) {
     const int idx = lane + i * 64;
     const int row = idx / CPR, dch = idx % CPR;
     if (wq0 + row < n_new) {
@@ -314,22 +319,22 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(
   }
 }
 
-int attention_q_tile_rows(int head_dim) { (void)head_dim; return 4 * 32 * 2; }
+int attention_q_tile_rows(int head_dim) { (void)head_dim; return 8 * 32; }
 
 template <int D>
 static void launch_attn_bf16(const void* qkv, const void* k_pool, const void* v_pool, void* o,
                              const Geometry& g, const BatchMeta& m, int layer, hipStream_t s) {
-  constexpr int NQ = 2, NW = 4;
+  constexpr int NW = 8;
   const size_t smem = (size_t)4 * kKT * D * sizeof(bf16);
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, NQ, NW>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, NW>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_set = true;
   }
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)D);
   dim3 grid((unsigned)((int64_t)m.n_attn_items * g.n_q_heads));
-  attn_bf16_kernel<D, NQ, NW><<<grid, NW * 64, smem, s>>>(
+  attn_bf16_kernel<D, NW><<<grid, NW * 64, smem, s>>>(
       (const bf16*)qkv, (const bf16*)k_pool, (const bf16*)v_pool, (bf16*)o, g.n_q_heads,
       g.n_kv_heads, g.kv_num_blocks, layer, m.cu_seqlens, m.cached_lens, m.block_tables,
       m.max_blocks, m.attn_items, scale_log2);
