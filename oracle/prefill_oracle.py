@@ -307,16 +307,21 @@ def layer_sampled_rows(shape: Shape, w: LayerWeights, x: torch.Tensor,
             if lo <= r < hi:
                 seq_of_row[r] = (lo, hi)
                 pos_of_row[r] = r - lo
-    out = torch.empty((len(rows), shape.hidden), dtype=F64)
+    # Queries, output projection and MLP for the sampled rows only, all rows at once per matmul;
+    # attention row by row (each row has its own causal extent).
+    rows = [int(r) for r in rows]
+    h_rows = h[rows]                                                             # [R, d]
+    q_rows = torch.matmul(h_rows, wqkv[:qw].transpose(0, 1)).reshape(len(rows), hq, dim)
+    attn_rows = torch.empty((len(rows), hq * dim), dtype=F64)
     for idx, r in enumerate(rows):
         lo, hi = seq_of_row[r]
         p = pos_of_row[r]
         pos = torch.tensor([p])
-        q = torch.matmul(h[r:r + 1], wqkv[:qw].transpose(0, 1)).reshape(1, hq, dim)
-        q = rope_rotate(q, pos, shape.rope_theta)
+        q = rope_rotate(q_rows[idx:idx + 1], pos, shape.rope_theta)
         o = causal_attention(q, k_rot[lo:lo + p + 1], v_raw[lo:lo + p + 1], pos)
-        xr = x[r:r + 1] + linear(o.reshape(1, hq * dim), w.w_o)
-        h2 = rmsnorm(xr, w.mlp_norm, shape.rms_eps)
-        act = silu_mul(linear(h2, w.w_gate_up))
-        out[idx] = (xr + linear(act, w.w_down))[0]
+        attn_rows[idx] = o.reshape(hq * dim)
+    xr = x[rows] + linear(attn_rows, w.w_o)
+    h2 = rmsnorm(xr, w.mlp_norm, shape.rms_eps)
+    act = silu_mul(linear(h2, w.w_gate_up))
+    out = xr + linear(act, w.w_down)
     return k_rot, v_raw, out

@@ -240,7 +240,7 @@ __device__ __forceinline__ void pp_mfma_and_loads(const PpFrags& f, f32x16 (&acc
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i][kk], f.b[j][kk], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j][kk], f.a[i][kk], acc[i][j], 0, 0, 0);
       if (load) {
         const int slot = kk * 4 + i;            // 0..15: slots 0..7 load A rows, 8..15 load W rows
         const int base_row = (w4 * 8 + (slot & 7)) * 8;
@@ -339,24 +339,58 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
   }
   if (group == 0) pp_barrier();
 
-  // Epilogue (accumulator layout as in the kernel above).
+  // Epilogue.  The MFMAs take the W fragment as their row operand, so each 32x32 accumulator is
+  // a block of C^T: lane l holds output row m = l%32 and, per register quad a, the four
+  // consecutive columns n = 8a + 4*(l/32) + (0..3).
+  if (RESID) {
+    // fp32 residual: one 16-byte read-modify-write per quad.
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i) {
+      const int m = m0 + wm * 128 + i * 32 + frag_row;
+      if (m >= M) continue;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn * 64 + j * 32 + frag_row;
+      for (int j = 0; j < 2; ++j) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        if (m < M && n < N) {
-          if (RESID) {
-            float* c = reinterpret_cast<float*>(Cout) + (int64_t)m * N + n;
-            *c = *c + acc[i][j][r];
-          } else {
-            reinterpret_cast<bf16*>(Cout)[(int64_t)m * N + n] = static_cast<bf16>(acc[i][j][r]);
-          }
+        for (int a = 0; a < 4; ++a) {
+          const int n = n0 + wn * 64 + j * 32 + 8 * a + 4 * half;
+          if (n >= N) continue;                     // N is a multiple of 8: quads are all-in or all-out
+          f32x4* c = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(Cout) + (int64_t)m * N + n);
+          f32x4 v = *c;
+#pragma unroll
+          for (int b = 0; b < 4; ++b) v[b] += acc[i][j][4 * a + b];
+          *c = v;
         }
       }
+    }
+  } else {
+    // bf16 output: each wave stages its 128x64 block in its own 16 KB of the (now idle) LDS
+    // stages as [128 rows][8 chunks of 8 bf16], chunk c of row r at position c ^ ((r>>1)&7), then
+    // stores whole 128-byte rows with 16-byte accesses (8 full cache lines per instruction).
+    bf16* region = (wave >> 1) == 0 ? sA0 : (wave >> 1) == 1 ? sA1 : (wave >> 1) == 2 ? sB0 : sB1;
+    region += (wave & 1) * (128 * 64);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = i * 32 + frag_row;
+      const int rkey = (row >> 1) & 7;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          bf16x4 v;
+#pragma unroll
+          for (int b = 0; b < 4; ++b) v[b] = static_cast<bf16>(acc[i][j][4 * a + b]);
+          *reinterpret_cast<bf16x4*>(region + row * 64 + (((j * 4 + a) ^ rkey) << 3) + 4 * half) = v;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);     // own wave's LDS writes have landed; no other wave touches the region
+    bf16* cbase = reinterpret_cast<bf16*>(Cout) + (int64_t)(m0 + wm * 128) * N + n0 + wn * 64;
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int idx = lane + it * 64;
+      const int row = idx >> 3, ch = idx & 7;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(region + row * 64 + ((ch ^ ((row >> 1) & 7)) << 3));
+      if (m0 + wm * 128 + row < M && n0 + wn * 64 + ch * 8 < N)
+        *reinterpret_cast<u32x4*>(cbase + (int64_t)row * N + ch * 8) = v;
     }
   }
 }
