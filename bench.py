@@ -62,6 +62,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--config", default="cfg2", help="cfg2 (default); other names are for exploration")
     ap.add_argument("--layers", type=int, default=0, help="override layer count (exploration only)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a 1 GiB device-to-device copy (known HBM traffic) for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -70,6 +73,16 @@ def main() -> int:
 
     import torch
     from paper_2602_16603_amd import binding as B, inputs as I, runner as R
+
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 5}))
+        return 0
 
     cfg = I.CONFIGS[args.config]
     spec, seed = cfg["shape"], cfg["seed"]
@@ -111,7 +124,8 @@ def main() -> int:
     step_flops = sum(per_layer) * spec.n_layers
     tflops = step_flops / (elapsed / args.steps) / 1e12
 
-    # Dominant kernel: the non-residual 256x256 bf16 MFMA GEMM (qkv_proj and gate_up_proj launches).
+    # Dominant kernel: gemm_bf16_pp_kernel<false>, the ping-pong 256x256 bf16 MFMA GEMM with bf16
+    # output (the qkv_proj and gate_up_proj launches; gate_up alone is 47% of a layer's FLOPs).
     dom_ops = (1, 6)
     dom_ms = [ms for o in dom_ops for ms in op_ms[o]]
     dom_flops = sum(per_layer[o] for o in dom_ops) / len(dom_ops)      # mean per launch
@@ -124,6 +138,15 @@ def main() -> int:
         if per_layer[o] > 0:
             per_op[name]["tflops"] = round(per_layer[o] / (avg * 1e-3) / 1e12, 1)
 
+    # HBM-side bytes per launch of the dominant kernel come from the committed rocprofv3 --pmc
+    # summary (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy); null when that file is absent
+    # or describes another workload.
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gemm_bf16_pp_cfg2_traffic.json")
+    if args.config == "cfg2" and not args.layers and os.path.exists(tpath):
+        with open(tpath) as fh:
+            traffic = json.load(fh).get("hbm_bytes_per_launch")
+
     out = {
         "metric": "prefill tokens/s, Llama-3-8B-shaped 4-layer stack, bf16, 1 GPU",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -135,9 +158,9 @@ def main() -> int:
                                f"check at every boundary", "seed": seed},
         "tflops": round(tflops, 1), "mfma_frac": round(tflops / BF16_MFMA_PEAK_TFLOPS, 4),
         "per_op": per_op,
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel<256,256,false> (qkv_proj, gate_up_proj)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_pp_kernel<false> (qkv_proj, gate_up_proj)",
                      "achieved": round(achieved, 1), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
                      "avg_launch_ms": round(dom_avg_ms, 4), "flops_per_launch": dom_flops},
     }
     if not args.no_cpu_baseline:
