@@ -54,6 +54,96 @@ def cpu_baseline(spec, seed, sample_tokens, sample_layers):
                       f"{spec.n_layers} layers (fp64 oracle); time scaled by {scale:g} to the full stack"}
 
 
+def percentile(values, q):
+    if not values:
+        return None
+    v = sorted(values)
+    return v[min(len(v) - 1, int(round(q * (len(v) - 1))))]
+
+
+def preemption_workload(seconds: float, seed: int = 4):
+    """cfg4: a 32768-token prompt always in flight on the 32-layer 8B shape while 128..1024-token
+    prompts arrive as a seeded Poisson process (20 req/s); every arrival preempts the long prompt
+    at the next boundary, runs, and the long prompt resumes.  Blocking time = signal ->
+    acknowledgement (paper Section 6.4).  Modes: operator-level checks (launch-ahead 2 and 1) and
+    fixed chunked prefill with chunk 512 / 2048 / 8192 (boundary = chunk end only)."""
+    import torch
+    from paper_2602_16603_amd import binding as B, eventloop as E, inputs as I, runner as R
+
+    spec = I.CONFIGS["cfg4"]["shape"]
+    long_n = I.CONFIGS["cfg4"]["lengths"][0]
+    weights = I.make_weights(spec, seed, torch.bfloat16, "cuda")
+    model = R.PrefillModel(spec, weights, B.FP_DTYPE_BF16, kv_num_blocks=long_n // 16 + 8 * 70 + 64,
+                           max_position=long_n)
+    long_hidden = I.make_hidden(long_n, spec.hidden, seed, torch.bfloat16, "cuda")
+    short_hidden = I.make_hidden(1024, spec.hidden, seed + 1, torch.bfloat16, "cuda")
+    arrivals = I.poisson_arrivals(20.0, seconds, seed)
+
+    # One uninterrupted long prefill with per-op timing: the layer time the latency is judged by.
+    task = model.begin(long_hidden, [long_n])
+    task.run_to_completion()
+    task.end()
+    task = model.begin(long_hidden, [long_n])
+    B.fp_prefill_set_timing(task.handle, True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    task.run_to_completion()
+    long_s = time.perf_counter() - t0
+    ops = B.fp_prefill_op_times(task.handle, spec.n_layers * 9)
+    task.end()
+    per_op = [statistics.fmean(ops[i::9]) for i in range(9)]
+    result = {"workload": f"cfg4: {spec.n_layers}-layer 8B shape, {long_n}-token prompt in flight, "
+                          f"{len(arrivals)} Poisson arrivals (20/s, 128-1024 tokens) over {seconds:g} s",
+              "long_prefill_uninterrupted_s": round(long_s, 4),
+              "long_prefill_tokens_per_s": round(long_n / long_s, 1),
+              "layer_ms": round(sum(per_op), 3), "slowest_op_ms": round(max(per_op), 3),
+              "op_ms": {n: round(v, 3) for n, v in zip(B.OP_NAMES, per_op)}, "modes": {}}
+
+    modes = [("op_level_ahead2", 0, 2), ("op_level_ahead1", 0, 1), ("chunk_512", 512, 2),
+             ("chunk_2048", 2048, 2), ("chunk_8192", 8192, 2)]
+    for name, chunk, ahead in modes:
+        pool = E.MixedPool(model, B.FP_BOUNDARY_EVERY_OP, launch_ahead=ahead)
+        state = {"longs": 0, "stop": False}
+
+        def reissue(req, state=state):
+            if req.name.startswith("L") and not state["stop"]:
+                state["longs"] += 1
+                loop.post_arrival(E.Request(f"L{state['longs']}", long_n, (long_hidden, chunk)))
+
+        # Fixed rule: a short request overtakes the long prompt; shorts run in arrival order.
+        loop = E.EventLoop(pool, priority=lambda r: (r.name.startswith("L"), r.order), on_complete=reissue)
+        shorts = [E.Request(f"s{i}", n, (short_hidden[:n], 0), arrival=t) for i, (t, n) in enumerate(arrivals)]
+        loop.post_arrival(E.Request("L0", long_n, (long_hidden, chunk)))
+        loop.step(5.0)
+        t_start = time.perf_counter()
+        E.feed_arrivals(loop, shorts)
+        while True:
+            loop.step(0.05)
+            n_short_done = sum(1 for r in loop.finished if r.name.startswith("s"))
+            if n_short_done == len(shorts) and time.perf_counter() - t_start >= seconds:
+                break
+            if time.perf_counter() - t_start > seconds + 60:
+                raise TimeoutError(f"preemption workload {name} did not drain")
+        state["stop"] = True
+        elapsed = time.perf_counter() - t_start
+        last = loop.running
+        if last is not None:                            # stop the background long prompt
+            pool.preempt(last.handle)
+        loop.close()                                    # joins the executor thread
+        if last is not None:
+            pool.finish(last.handle)
+        lat_us = [x * 1e6 for x, who in zip(loop.preempt_latency_s, loop.preempt_victims) if who.startswith("L")]
+        ttft_ms = [(r.t_finished - r.t_arrived) * 1e3 for r in loop.finished if r.name.startswith("s")]
+        result["modes"][name] = {
+            "preemptions": len(lat_us),
+            "blocking_us": {"p50": round(percentile(lat_us, 0.5) or 0, 1), "p99": round(percentile(lat_us, 0.99) or 0, 1),
+                            "max": round(max(lat_us) if lat_us else 0, 1)},
+            "short_ttft_ms": {"p50": round(percentile(ttft_ms, 0.5) or 0, 2), "p99": round(percentile(ttft_ms, 0.99) or 0, 2)},
+            "long_prompts_completed": state["longs"], "elapsed_s": round(elapsed, 3)}
+    model.close()
+    return result
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +152,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--config", default="cfg2", help="cfg2 (default); other names are for exploration")
     ap.add_argument("--layers", type=int, default=0, help="override layer count (exploration only)")
+    ap.add_argument("--preempt-seconds", type=float, default=2.0,
+                    help="length of each mode of the preemption-latency workload (cfg4); 0 skips it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device-to-device copy (known HBM traffic) for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -169,6 +261,10 @@ def main() -> int:
         out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 2)
         out["cpu_baseline"]["seconds"] = round(out["cpu_baseline"]["seconds"], 2)
     model.close()
+    del model, weights, hidden
+    torch.cuda.empty_cache()
+    if args.preempt_seconds > 0 and args.config == "cfg2" and not args.layers:
+        out["preemption"] = preemption_workload(args.preempt_seconds)
     print(json.dumps(out))
     return 0
 

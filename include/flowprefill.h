@@ -181,7 +181,9 @@ fp_status fp_prefill_op_times(fp_prefill* task, float* ms_out /*host*/, int32_t 
                               int32_t* n_out /*host*/);
 
 /* Ends a task in any state except while an advance is running: returns its workspace to the
- * model's cache and frees the KV blocks the library allocated for it.                            */
+ * model's cache and frees the KV blocks the library allocated for it.  "Running" lasts until
+ * fp_prefill_advance has RETURNED in its thread: after fp_preempt reports FP_PREEMPTED from
+ * another thread, wait for that advance call to return before ending the task.                   */
 void fp_prefill_end(fp_prefill* task);
 
 /* Single-operator entry points used by the unit tests and the roofline measurement: each

@@ -42,9 +42,11 @@ class EventLoop:
     PREEMPTED), preempt(handle) -> status (blocking until acknowledged; DONE if the task finished
     first), resume(handle), finish(handle)."""
 
-    def __init__(self, pool, priority: Callable[[Request], Any] = default_priority):
+    def __init__(self, pool, priority: Callable[[Request], Any] = default_priority,
+                 on_complete: Optional[Callable[[Request], None]] = None):
         self.pool = pool
         self.priority = priority
+        self.on_complete = on_complete           # e.g. re-issue a background request
         self.events: "queue.Queue[Tuple[str, Optional[Request]]]" = queue.Queue()
         self.jobs: "queue.Queue[Optional[Request]]" = queue.Queue()
         self.waiting: List[Request] = []         # Q_w
@@ -54,6 +56,7 @@ class EventLoop:
         self.commands: List[str] = []
         self.rounds = 0
         self.preempt_latency_s: List[float] = []
+        self.preempt_victims: List[str] = []     # name of the task each latency sample belongs to
         self._early_done = set()
         self._arrivals = 0
         self._worker = threading.Thread(target=self._work, daemon=True)
@@ -98,6 +101,7 @@ class EventLoop:
             t0 = time.perf_counter()
             status = self.pool.preempt(victim.handle)
             self.preempt_latency_s.append(time.perf_counter() - t0)
+            self.preempt_victims.append(victim.name)
             if status == PREEMPTED:
                 self.commands.append(f"preempt {victim.name}")
                 self.preempted.append(victim)
@@ -122,6 +126,8 @@ class EventLoop:
         self.finished.append(req)
         if self.running is req:
             self.running = None
+        if self.on_complete is not None:
+            self.on_complete(req)
 
     # ---- main loop ----
     def run(self, n_requests: int, timeout_s: float = 600.0) -> None:
@@ -136,6 +142,15 @@ class EventLoop:
             except queue.Empty:
                 continue
             self._round(kind, req)
+
+    def step(self, timeout_s: float) -> bool:
+        """Handles at most one event; False if none arrived within the timeout."""
+        try:
+            kind, req = self.events.get(timeout=timeout_s)
+        except queue.Empty:
+            return False
+        self._round(kind, req)
+        return True
 
     def close(self) -> None:
         self.jobs.put(None)
@@ -158,6 +173,20 @@ def feed_arrivals(loop: EventLoop, requests: List[Request]) -> threading.Thread:
     return th
 
 
+def _advance_or_parked(task) -> int:
+    """Runs the task to its next stop.  The scheduler may have parked the task between making it
+    current and this thread reaching advance (fp_preempt on an idle task parks it at once); the
+    library then refuses the advance with FP_ERR_STATE, which here simply means PREEMPTED."""
+    from . import binding as B
+    try:
+        status, _ = task.advance()
+        return status
+    except B.FlowPrefillError as exc:
+        if exc.status == B.FP_ERR_STATE:
+            return PREEMPTED
+        raise
+
+
 class PrefillPool:
     """The execution pool over the HIP library: at most one task runs; parked tasks keep their
     workspace and KV blocks (Section 4)."""
@@ -170,8 +199,96 @@ class PrefillPool:
         return self.model.begin(req.payload, [req.n_tokens], boundary_mask=self.boundary_mask)
 
     def run(self, task) -> int:
-        status, _ = task.advance()
-        return status
+        return _advance_or_parked(task)
+
+    def preempt(self, task) -> int:
+        return task.preempt()
+
+    def resume(self, task) -> None:
+        task.resume()
+
+    def finish(self, task) -> None:
+        task.end()
+
+
+class ChunkedPrefillTask:
+    """Fixed chunked prefill of one prompt (the baseline of Section 3.1 / Fig. 2): the prompt is
+    run `chunk` tokens at a time through the whole stack, every chunk attending to the KV its
+    predecessors left in the paged cache; the scheduler can take the GPU only between chunks.
+    Host logic only -- each chunk is an ordinary task of the library with no operator-level
+    checks."""
+
+    def __init__(self, model, hidden, n_tokens: int, chunk: int):
+        from . import binding as B
+        self._B = B
+        self.model, self.hidden, self.n, self.chunk = model, hidden, n_tokens, chunk
+        self.blocks = B.fp_kv_alloc(model.handle, (n_tokens + 15) // 16)
+        self.table = self.blocks.reshape(1, -1)
+        self.done_tokens = 0
+        self.cond = threading.Condition()
+        self.signal = False
+        self.parked = False
+        self.finished = False
+
+    def run(self) -> int:
+        B = self._B
+        while self.done_tokens < self.n:
+            with self.cond:                        # chunk boundary: the only place a preempt lands
+                if self.signal:
+                    self.signal = False
+                    self.parked = True
+                    self.cond.notify_all()
+                    return PREEMPTED
+            lo, hi = self.done_tokens, min(self.n, self.done_tokens + self.chunk)
+            task = self.model.begin(self.hidden[lo:hi], [hi - lo], cached=[lo], block_tables=self.table,
+                                    boundary_mask=B.FP_BOUNDARY_NONE)
+            task.run_to_completion()
+            task.end()
+            self.done_tokens = hi
+        with self.cond:
+            self.finished = True
+            self.signal = False
+            self.cond.notify_all()
+        return DONE
+
+    def preempt(self) -> int:
+        with self.cond:
+            if not self.finished and not self.parked:
+                self.signal = True
+                self.cond.wait_for(lambda: self.parked or self.finished)
+            return DONE if self.finished else PREEMPTED
+
+    def resume(self) -> None:
+        with self.cond:
+            self.parked = False
+
+    def end(self) -> None:
+        if self.blocks is not None:
+            self._B.fp_kv_free(self.model.handle, self.blocks)
+            self.blocks = None
+
+
+class MixedPool:
+    """Execution pool for the preemption workload: requests whose payload is a
+    (hidden, chunk) pair with chunk > 0 run as fixed chunked prefill, all others as one
+    operator-preemptible task."""
+
+    def __init__(self, model, boundary_mask: int, launch_ahead: int = 2):
+        self.model, self.boundary_mask, self.launch_ahead = model, boundary_mask, launch_ahead
+
+    def submit(self, req: Request):
+        hidden, chunk = req.payload
+        if chunk:
+            return ChunkedPrefillTask(self.model, hidden, req.n_tokens, chunk)
+        task = self.model.begin(hidden, [req.n_tokens], boundary_mask=self.boundary_mask)
+        from . import binding as B
+        B.fp_prefill_set_launch_ahead(task.handle, self.launch_ahead)
+        return task
+
+    def run(self, task) -> int:
+        if isinstance(task, ChunkedPrefillTask):
+            return task.run()
+        return _advance_or_parked(task)
 
     def preempt(self, task) -> int:
         return task.preempt()
