@@ -30,7 +30,10 @@ namespace fp {
 // rescaled) when some row's maximum has grown by more than 2^8 since the reference was set, so
 // exp2 arguments stay <= 8 and almost every tile skips the D/32*16 rescale multiplies.
 //
-// LDS layouts (16-byte chunks; the LDS has 64 banks and serves b128 reads 16 lanes at a time):
+// LDS layouts (16-byte chunks).  Measured on gfx950: 64 banks; a ds_read_b128 is served one
+// half-wave after the other, and a half-wave costs max(2, most lanes on one 16-byte bank group)
+// clocks -- so a pattern is conflict-free when each half-wave puts at most two lanes on any
+// 16-byte slot modulo 256 bytes:
 //   K tile [64 keys][D]      chunk c of key row r stored at c ^ key(r), key chosen so that the
 //                            16 rows one read phase touches fall on 16 distinct bank groups
 //   V tile [4 blocks][D][16] the two 16-byte halves of channel row d swapped when d & 8
@@ -165,19 +168,23 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
     if (key0 <= wave_q_max && wq0 < n_new) {
       const bf16* cK = sK + cur * kKT * D;
       const bf16* cV = sV + cur * kKT * D;
-      // ---- S^T = K Q^T ----
+      // ---- S^T = K Q^T ----  (the eight K fragments of a 32-key block are fetched before the
+      // MFMAs that consume them -- the scheduling fence keeps the compiler from sinking each read
+      // next to its MFMA -- so LDS latency is paid once per block, not once per MFMA)
       f32x16 sacc[2];
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
+        const bf16* krow = cK + (rb * 32 + pi_row) * D;
+        bf16x8 kf[KK];
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+          kf[kk] = *reinterpret_cast<const bf16x8*>(krow + (((kk * 2 + lh) ^ k_swz) << 3));
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[rb][r] = 0.f;
-        const bf16* krow = cK + (rb * 32 + pi_row) * D;
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          const int dch = kk * 2 + lh;
-          bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + ((dch ^ k_swz) << 3));
-          sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[rb], 0, 0, 0);
-        }
+        for (int kk = 0; kk < KK; ++kk)
+          sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sacc[rb], 0, 0, 0);
       }
       // ---- online softmax for this lane's query column ----
       if (key0 + kKT - 1 > wave_q_min) {              // tile straddles the diagonal: mask
@@ -220,16 +227,19 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
         pf[c] = __builtin_convertvector(pv, bf16x8);
       }
       l_run += psum;
-      // ---- O^T += V^T P^T ----
+      // ---- O^T += V^T P^T ----  (same: the four V fragments of a channel block first)
 #pragma unroll
       for (int i = 0; i < DB; ++i) {
         const int d = i * 32 + lq;
         const int phys = d * 2 + (lh ^ ((d >> 3) & 1));
+        bf16x8 vf[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          bf16x8 vf = *reinterpret_cast<const bf16x8*>(cV + c * (D * kKvBlock) + (phys << 3));
-          oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[c], oacc[i], 0, 0, 0);
-        }
+        for (int c = 0; c < 4; ++c)
+          vf[c] = *reinterpret_cast<const bf16x8*>(cV + c * (D * kKvBlock) + (phys << 3));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c], pf[c], oacc[i], 0, 0, 0);
       }
     }
     if (t + 1 < n_tiles) store_tile(cur ^ 1);
