@@ -136,10 +136,12 @@ fp_status fp_prefill_begin(fp_model* model, const void* hidden_in /*device*/,
  * another thread meanwhile.  FP_ERR_STATE if the task is parked or already done.                 */
 fp_status fp_prefill_advance(fp_prefill* task, int32_t max_ops, int32_t* ops_done /*host*/);
 
-/* How many operators may be enqueued on the stream beyond the one known complete (>= 1).  With
- * k the host launches operator i only after operator i-k has completed, so a signal is honoured
+/* How many operators may be enqueued on the stream beyond the one known complete.  With k >= 1
+ * the host launches operator i only after operator i-k has completed, so a signal is honoured
  * within k operators.  Default 2 (no launch bubble; at most the running and one queued operator
- * finish before the acknowledgement).                                                            */
+ * finish before the acknowledgement).  k = 0 removes the bound (and the per-operator event): the
+ * host enqueues as fast as it can and a signal is honoured only after everything enqueued so far
+ * has run -- meant for short requests whose operators last tens of microseconds.                 */
 fp_status fp_prefill_set_launch_ahead(fp_prefill* task, int32_t k);
 
 /* "preempt" (Section 5.1, Fig. 6): thread-safe.  Sets the task's signal and blocks until the

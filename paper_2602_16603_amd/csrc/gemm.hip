@@ -2,6 +2,8 @@
 // FlowPrefill Eq. (1) and the operators qkv_proj / o_proj / gate_up_proj / down_proj of
 // Section 5.1.  bf16 path: MFMA 32x32x16 tiles with fp32 accumulation, LDS-staged and
 // double-buffered.  fp32 path: a plain LDS-tiled FMA kernel (debug).
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -261,11 +263,17 @@ __device__ __forceinline__ void pp_barrier() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
-template <bool RESID>
+// EPI selects the epilogue: bf16 store, fp32 residual read-modify-write, or (split-K) fp32
+// partial sums to a workspace [split][M][N] that splitk_reduce_kernel adds up in a fixed order.
+enum { kEpiBf16 = 0, kEpiResidual = 1, kEpiPartial = 2 };
+
+template <int EPI>
 __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restrict__ A,
                                                            const bf16* __restrict__ W,
                                                            void* __restrict__ Cout, int M, int N,
-                                                           int K, int tiles_m, int tiles_n) {
+                                                           int K, int tiles_m, int tiles_n,
+                                                           int kt_per_split) {
+  constexpr bool RESID = EPI == kEpiResidual;
   constexpr int BM = 256, BN = 256;
   __shared__ __attribute__((aligned(1024))) bf16 sA0[BM * kBK];
   __shared__ __attribute__((aligned(1024))) bf16 sA1[BM * kBK];
@@ -278,8 +286,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
   const int group = wave >> 2;
   const int wm = wave & 1, wn = wave >> 1;           // 2 x 4 waves, wave tile 128 x 64
   int tile_m, tile_n;
-  tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int n_tiles = tiles_m * tiles_n;
+  const int split = blockIdx.x / n_tiles;            // which K range (0 unless split-K)
+  tile_of_workgroup(blockIdx.x - split * n_tiles, tiles_m, tiles_n, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int kt_first = split * kt_per_split;
+  const int kt_count = min(kt_per_split, K / kBK - kt_first);
+  const int kbyte0 = kt_first * kBK * 2;
 
   // Per-lane byte offsets of the DMA sources inside the tile's row panel (the same for the A
   // and the W panel: both have K as row stride).  The four waves of group 1 load whole k-tiles:
@@ -305,10 +318,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int kt_count = K / kBK;
   if (group == 1) {
-    pp_issue_tile(rsrc_a, rsrc_w, 0, voff, sA0, sB0, w4);
-    if (kt_count > 1) pp_issue_tile(rsrc_a, rsrc_w, kBK * 2, voff, sA1, sB1, w4);
+    pp_issue_tile(rsrc_a, rsrc_w, kbyte0, voff, sA0, sB0, w4);
+    if (kt_count > 1) pp_issue_tile(rsrc_a, rsrc_w, kbyte0 + kBK * 2, voff, sA1, sB1, w4);
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
   }
   pp_barrier();
@@ -328,8 +340,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
     // -- compute phase --
     // Both groups have finished reading this stage (group 0 one phase ago, group 1 just now):
     // group 1 refills it with k-tile t+2 while it computes.
-    pp_mfma_and_loads(f, acc, group == 1 && t + 2 < kt_count, rsrc_a, rsrc_w, (t + 2) * kBK * 2,
-                      voff, sA, sB, w4);
+    pp_mfma_and_loads(f, acc, group == 1 && t + 2 < kt_count, rsrc_a, rsrc_w,
+                      kbyte0 + (t + 2) * kBK * 2, voff, sA, sB, w4);
     pp_barrier();
   };
 
@@ -343,8 +355,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
   // Epilogue.  The MFMAs take the W fragment as their row operand, so each 32x32 accumulator is
   // a block of C^T: lane l holds output row m = l%32 and, per register quad a, the four
   // consecutive columns n = 8a + 4*(l/32) + (0..3).
-  if (RESID) {
-    // fp32 residual: one 16-byte read-modify-write per quad.
+  if (EPI != kEpiBf16) {
+    // fp32 residual: one 16-byte read-modify-write per quad.  Split-K partial: a plain 16-byte
+    // store into this split's [M][N] slab of the workspace.
+    float* cf = reinterpret_cast<float*>(Cout) + (EPI == kEpiPartial ? (int64_t)split * M * N : 0);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int m = m0 + wm * 128 + i * 32 + frag_row;
@@ -355,10 +369,11 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
         for (int a = 0; a < 4; ++a) {
           const int n = n0 + wn * 64 + j * 32 + 8 * a + 4 * half;
           if (n >= N) continue;                     // N is a multiple of 8: quads are all-in or all-out
-          f32x4* c = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(Cout) + (int64_t)m * N + n);
-          f32x4 v = *c;
+          f32x4* c = reinterpret_cast<f32x4*>(cf + (int64_t)m * N + n);
+          f32x4 v;
+          if (RESID) v = *c;
 #pragma unroll
-          for (int b = 0; b < 4; ++b) v[b] += acc[i][j][4 * a + b];
+          for (int b = 0; b < 4; ++b) v[b] = RESID ? v[b] + acc[i][j][4 * a + b] : acc[i][j][4 * a + b];
           *c = v;
         }
       }
@@ -396,11 +411,65 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
   }
 }
 
+// Split-K reduction: out[m][n] = sum over splits (in index order: deterministic) of the fp32
+// partials, added into the fp32 residual or rounded to bf16.  One thread per 8 outputs.
 template <bool RESID>
-static void launch_bf16_pp(const bf16* a, const bf16* w, void* c, int m, int n, int k, hipStream_t s) {
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part,
+                                                            void* __restrict__ out, int64_t mn8,
+                                                            int64_t mn, int splits) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= mn8) return;
+  f32x8 acc = Vec8<float>::load(part + i * 8);
+  for (int z = 1; z < splits; ++z) {
+    const f32x8 v = Vec8<float>::load(part + z * mn + i * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += v[e];
+  }
+  if (RESID) {
+    float* o = reinterpret_cast<float*>(out) + i * 8;
+    const f32x8 x = Vec8<float>::load(o);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += x[e];
+    Vec8<float>::store(o, acc);
+  } else {
+    Vec8<bf16>::store(reinterpret_cast<bf16*>(out) + i * 8, acc);
+  }
+}
+
+// How many K ranges to cut a problem into so that a launch has about one workgroup per CU:
+// only when the 256x256 tiles alone leave most of the chip idle, and never below 8 k-tiles
+// (512 columns) per range.  1 = no split.
+static int pp_splits(int64_t m, int64_t n, int64_t k) {
+  const int64_t tiles = ((m + 255) / 256) * ((n + 255) / 256);
+  if (tiles <= 0 || tiles >= 160) return 1;
+  int s = (int)std::min<int64_t>(16, 256 / tiles);
+  while (s > 1 && (k / kBK) / s < 8) --s;
+  return s;
+}
+
+size_t gemm_workspace_bytes(int dtype, int64_t m, int64_t n, int64_t k) {
+  if (dtype != 1 || k % kBK != 0) return 0;
+  const int s = pp_splits(m, n, k);
+  return s > 1 ? (size_t)s * m * n * sizeof(float) : 0;
+}
+
+template <bool RESID>
+static void launch_bf16_pp(const bf16* a, const bf16* w, void* c, int m, int n, int k, int splits,
+                           float* workspace, hipStream_t s) {
   const int tiles_m = (m + 255) / 256, tiles_n = (n + 255) / 256;
-  gemm_bf16_pp_kernel<RESID><<<dim3((unsigned)(tiles_m * tiles_n)), 512, 0, s>>>(a, w, c, m, n, k,
-                                                                               tiles_m, tiles_n);
+  const int kt = k / kBK;
+  if (splits <= 1) {
+    gemm_bf16_pp_kernel<RESID ? kEpiResidual : kEpiBf16>
+        <<<dim3((unsigned)(tiles_m * tiles_n)), 512, 0, s>>>(a, w, c, m, n, k, tiles_m, tiles_n, kt);
+    return;
+  }
+  const int per = (kt + splits - 1) / splits;
+  const int used = (kt + per - 1) / per;             // every launched split has at least one k-tile
+  gemm_bf16_pp_kernel<kEpiPartial><<<dim3((unsigned)(tiles_m * tiles_n * used)), 512, 0, s>>>(
+      a, w, workspace, m, n, k, tiles_m, tiles_n, per);
+  const int64_t mn = (int64_t)m * n;
+  splitk_reduce_kernel<RESID><<<dim3((unsigned)((mn / 8 + 255) / 256)), 256, 0, s>>>(workspace, c, mn / 8,
+                                                                                   mn, used);
 }
 
 template <int BM, int BN, int WGM, int WGN, bool RESID>
@@ -469,7 +538,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 }
 
 void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
-                 int64_t k, int residual, hipStream_t s) {
+                 int64_t k, int residual, void* workspace, size_t workspace_bytes, hipStream_t s) {
   if (m == 0 || n == 0) return;
   if (dtype == 0) {
     dim3 grid((unsigned)((n + 63) / 64), (unsigned)((m + 63) / 64));
@@ -483,12 +552,15 @@ void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, in
   }
   const bf16* pa = (const bf16*)a;
   const bf16* pw = (const bf16*)w;
-  // Large problems with K a multiple of 64: the ping-pong DMA kernel on 256x256 tiles.  Small
-  // or odd-K problems: the register-staged kernel on 128x128 tiles.
+  // K a multiple of 64 and enough 256x256 tiles (or enough K to split) to occupy the chip: the
+  // ping-pong DMA kernel, split over K when the caller's workspace allows.  Otherwise (tiny or
+  // odd-K problems): the register-staged kernel on 128x128 tiles.
   const int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
-  if (k % kBK == 0 && big_tiles >= 192) {
-    if (residual) launch_bf16_pp<true>(pa, pw, c, (int)m, (int)n, (int)k, s);
-    else launch_bf16_pp<false>(pa, pw, c, (int)m, (int)n, (int)k, s);
+  int splits = k % kBK == 0 ? pp_splits(m, n, k) : 1;
+  if (splits > 1 && (size_t)splits * m * n * sizeof(float) > workspace_bytes) splits = 1;
+  if (k % kBK == 0 && big_tiles * splits >= 96) {
+    if (residual) launch_bf16_pp<true>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, s);
+    else launch_bf16_pp<false>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, s);
   } else {
     if (residual) launch_bf16_cfg<128, 128, 2, 2, true>(pa, pw, c, (int)m, (int)n, (int)k, s);
     else launch_bf16_cfg<128, 128, 2, 2, false>(pa, pw, c, (int)m, (int)n, (int)k, s);

@@ -44,8 +44,12 @@ void launch_rope_kvwrite(int dtype, void* qkv, const float* rope_cos, const floa
 void launch_attention(int dtype, const void* qkv, const void* k_pool, const void* v_pool,
                       void* o, const Geometry& g, const BatchMeta& m, int layer, hipStream_t s);
 // C[M,N] = A[M,K] W[N,K]^T  (residual == 0, C in the storage dtype), or C_f32 += ... (residual).
+// `workspace` (device, may be null) holds split-K partial sums for problems too small to fill the
+// chip with output tiles alone; gemm_workspace_bytes says how much such a problem wants (0 if
+// it would not split).  Without enough workspace the problem runs unsplit.
 void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
-                 int64_t k, int residual, hipStream_t s);
+                 int64_t k, int residual, void* workspace, size_t workspace_bytes, hipStream_t s);
+size_t gemm_workspace_bytes(int dtype, int64_t m, int64_t n, int64_t k);
 
 // Gathers positions 0..len-1 of one sequence (block table row `table_dev`, device) of one layer
 // into contiguous k_out/v_out [len, Hkv, D].

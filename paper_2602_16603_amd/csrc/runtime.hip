@@ -86,6 +86,8 @@ struct fp_prefill {
   // carved out of ws:
   float* x = nullptr;
   void *h = nullptr, *qkv = nullptr, *o = nullptr, *gu = nullptr, *act = nullptr;
+  void* splitk = nullptr;              // split-K partial sums (0 bytes when no GEMM of this task splits)
+  size_t splitk_bytes = 0;
   fp::BatchMeta meta{};
   // cursor and gate
   int32_t cursor = 0;                  // next operator, 0 .. n_layers*9
@@ -114,7 +116,7 @@ fp_status launch_op(fp_prefill* t, int32_t index) {
   hipStream_t s = m->stream;
   switch (op) {
     case 0: fp::launch_rmsnorm(dt, t->x, w.attn_norm, t->h, T, d, sh.rms_eps, s); break;
-    case 1: fp::launch_gemm(dt, t->h, w.w_qkv, t->qkv, T, m->geo.qkv_width(), d, 0, s); break;
+    case 1: fp::launch_gemm(dt, t->h, w.w_qkv, t->qkv, T, m->geo.qkv_width(), d, 0, t->splitk, t->splitk_bytes, s); break;
     case 2:
       fp::launch_rope_kvwrite(dt, t->qkv, m->rope_cos, m->rope_sin, m->geo, t->meta, layer,
                               m->k_pool, m->v_pool, s);
@@ -122,11 +124,11 @@ fp_status launch_op(fp_prefill* t, int32_t index) {
     case 3:
       fp::launch_attention(dt, t->qkv, m->k_pool, m->v_pool, t->o, m->geo, t->meta, layer, s);
       break;
-    case 4: fp::launch_gemm(dt, t->o, w.w_o, t->x, T, d, qd, 1, s); break;
+    case 4: fp::launch_gemm(dt, t->o, w.w_o, t->x, T, d, qd, 1, t->splitk, t->splitk_bytes, s); break;
     case 5: fp::launch_rmsnorm(dt, t->x, w.mlp_norm, t->h, T, d, sh.rms_eps, s); break;
-    case 6: fp::launch_gemm(dt, t->h, w.w_gate_up, t->gu, T, 2 * F, d, 0, s); break;
+    case 6: fp::launch_gemm(dt, t->h, w.w_gate_up, t->gu, T, 2 * F, d, 0, t->splitk, t->splitk_bytes, s); break;
     case 7: fp::launch_silu_mul(dt, t->gu, t->act, T, F, s); break;
-    case 8: fp::launch_gemm(dt, t->act, w.w_down, t->x, T, d, F, 1, s); break;
+    case 8: fp::launch_gemm(dt, t->act, w.w_down, t->x, T, d, F, 1, t->splitk, t->splitk_bytes, s); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess)
@@ -392,6 +394,10 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   auto carve = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
   const size_t o_x = carve(Tn * d * 4), o_h = carve(Tn * d * e), o_qkv = carve(Tn * W * e),
                o_o = carve(Tn * qd * e), o_gu = carve(Tn * 2 * F * e), o_act = carve(Tn * F * e);
+  const size_t sk_bytes = std::max(
+      std::max(fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)W, (int64_t)d), fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)d, (int64_t)qd)),
+      std::max(fp::gemm_workspace_bytes(sh.dtype, T, 2 * (int64_t)F, (int64_t)d), fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)d, (int64_t)F)));
+  const size_t o_sk = carve(sk_bytes);
   const size_t n_int = tok_seq.size() + tok_pos.size() + t->cu.size() + t->cached.size() +
                        t->tables.size() + kv_items.size() + attn_items.size();
   const size_t o_int = carve((n_int + 16) * 4);
@@ -403,6 +409,7 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   }
   char* base = static_cast<char*>(t->ws.base);
   t->x = reinterpret_cast<float*>(base + o_x);
+  t->splitk = sk_bytes ? base + o_sk : nullptr; t->splitk_bytes = sk_bytes;
   t->h = base + o_h; t->qkv = base + o_qkv; t->o = base + o_o; t->gu = base + o_gu; t->act = base + o_act;
 
   std::vector<int32_t> ints;
@@ -450,7 +457,7 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
 }
 
 fp_status fp_prefill_set_launch_ahead(fp_prefill* t, int32_t k) {
-  if (!t || k < 1 || k > kEventRing) return fail(FP_ERR_INVALID, "launch_ahead must be 1..%d", kEventRing);
+  if (!t || k < 0 || k > kEventRing) return fail(FP_ERR_INVALID, "launch_ahead must be 0..%d", kEventRing);
   std::lock_guard<std::mutex> lk(t->mu);
   if (t->state == TaskState::Running) return fail(FP_ERR_STATE, "task is running");
   t->launch_ahead = k;
@@ -489,7 +496,7 @@ fp_status fp_prefill_advance(fp_prefill* t, int32_t max_ops, int32_t* ops_done) 
   while (t->cursor < total && issued < max_ops) {
     // Bound how far the host runs ahead of the device: operator i is launched only once
     // operator i - launch_ahead has completed.
-    if (issued >= t->launch_ahead) {
+    if (t->launch_ahead > 0 && issued >= t->launch_ahead) {
       hipError_t e = hipEventSynchronize(t->ring[(issued - t->launch_ahead) % kEventRing]);
       if (e != hipSuccess) { result = fail(FP_ERR_DEVICE, "event wait: %s", hipGetErrorString(e)); break; }
     }
@@ -514,7 +521,7 @@ fp_status fp_prefill_advance(fp_prefill* t, int32_t max_ops, int32_t* ops_done) 
     fp_status st = launch_op(t, t->cursor);
     if (st != FP_OK) { result = st; break; }
     if (t->timing) { (void)hipEventRecord(t->tev[issued + 1], s); t->timed_ops = issued + 1; }
-    (void)hipEventRecord(t->ring[issued % kEventRing], s);
+    if (t->launch_ahead > 0) (void)hipEventRecord(t->ring[issued % kEventRing], s);
     t->cursor++;
     issued++;
   }
@@ -649,7 +656,7 @@ fp_status fp_op_gemm(int32_t dtype, const void* a, const void* w, void* c, int64
   if (!a || !w || !c || m <= 0 || n <= 0 || k <= 0 || (k % 8) || (n % 8) || m > INT32_MAX ||
       n > INT32_MAX || k > INT32_MAX || (dtype != 0 && dtype != 1))
     return fail(FP_ERR_INVALID, "fp_op_gemm: bad size, alignment or dtype");
-  fp::launch_gemm(dtype, a, w, c, m, n, k, residual, reinterpret_cast<hipStream_t>(hip_stream));
+  fp::launch_gemm(dtype, a, w, c, m, n, k, residual, nullptr, 0, reinterpret_cast<hipStream_t>(hip_stream));
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? FP_OK : fail(FP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(e));
 }

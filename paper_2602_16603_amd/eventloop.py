@@ -273,8 +273,9 @@ class MixedPool:
     (hidden, chunk) pair with chunk > 0 run as fixed chunked prefill, all others as one
     operator-preemptible task."""
 
-    def __init__(self, model, boundary_mask: int, launch_ahead: int = 2):
+    def __init__(self, model, boundary_mask: int, launch_ahead: int = 2, short_tokens: int = 2048):
         self.model, self.boundary_mask, self.launch_ahead = model, boundary_mask, launch_ahead
+        self.short_tokens = short_tokens     # requests up to this size run with unbounded launch-ahead
 
     def submit(self, req: Request):
         hidden, chunk = req.payload
@@ -282,7 +283,7 @@ class MixedPool:
             return ChunkedPrefillTask(self.model, hidden, req.n_tokens, chunk)
         task = self.model.begin(hidden, [req.n_tokens], boundary_mask=self.boundary_mask)
         from . import binding as B
-        B.fp_prefill_set_launch_ahead(task.handle, self.launch_ahead)
+        B.fp_prefill_set_launch_ahead(task.handle, 0 if req.n_tokens <= self.short_tokens else self.launch_ahead)
         return task
 
     def run(self, task) -> int:

@@ -134,6 +134,25 @@ def test_8b_head_shapes_small_twin_bf16():
     model.close()
 
 
+@pytest.mark.parametrize("lengths", [[128], [512, 40], [1024]])
+def test_short_requests_8b_shape_use_split_k(lengths):
+    """The 128..1024-token requests of the preemption workload: too few 256x256 output tiles to
+    fill the chip, so the projections are split over K and reduced in a fixed order."""
+    spec = I.LLAMA3_8B.with_layers(1)
+    total = sum(lengths)
+    model, weights = build(spec, 26, "bf16", total_tokens=total, max_position=1024)
+    hidden = I.make_hidden(total, spec.hidden, 26, torch.bfloat16, "cpu")
+    task = model.begin(hidden.cuda(), lengths)
+    task.run_to_completion()
+    check_against_oracle(spec, weights, hidden, lengths, task, "bf16")
+    again = model.begin(hidden.cuda(), lengths)          # fixed reduction order: same bits every run
+    again.run_to_completion()
+    assert torch.equal(task.hidden(), again.hidden())
+    task.end()
+    again.end()
+    model.close()
+
+
 def test_packed_equals_alone_on_gpu_bf16():
     spec = I.TINY
     lengths = [90, 270, 33]
