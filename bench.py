@@ -65,8 +65,11 @@ def preemption_workload(seconds: float, seed: int = 4):
     """cfg4: a 32768-token prompt always in flight on the 32-layer 8B shape while 128..1024-token
     prompts arrive as a seeded Poisson process (20 req/s); every arrival preempts the long prompt
     at the next boundary, runs, and the long prompt resumes.  Blocking time = signal ->
-    acknowledgement (paper Section 6.4).  Modes: operator-level checks (launch-ahead 2 and 1) and
-    fixed chunked prefill with chunk 512 / 2048 / 8192 (boundary = chunk end only)."""
+    acknowledgement (paper Section 6.4).  Modes: checks after every operator (launch-ahead 2 and
+    1), after the paper's five core operators only, after every layer only (the layer-level
+    comparison of Section 6.4), fixed chunked prefill with chunk 512 / 2048 / 8192 (boundary =
+    chunk end only), and operator-level checks inside chunks of 4096 / 8192 / 16384 tokens (the
+    combination of Section 6.5)."""
     import torch
     from paper_2602_16603_amd import binding as B, eventloop as E, inputs as I, runner as R
 
@@ -99,10 +102,15 @@ def preemption_workload(seconds: float, seed: int = 4):
               "layer_ms": round(sum(per_op), 3), "slowest_op_ms": round(max(per_op), 3),
               "op_ms": {n: round(v, 3) for n, v in zip(B.OP_NAMES, per_op)}, "modes": {}}
 
-    modes = [("op_level_ahead2", 0, 2), ("op_level_ahead1", 0, 1), ("chunk_512", 512, 2),
-             ("chunk_2048", 2048, 2), ("chunk_8192", 8192, 2)]
-    for name, chunk, ahead in modes:
-        pool = E.MixedPool(model, B.FP_BOUNDARY_EVERY_OP, launch_ahead=ahead)
+    modes = [("op_level_ahead2", 0, 2, B.FP_BOUNDARY_EVERY_OP), ("op_level_ahead1", 0, 1, B.FP_BOUNDARY_EVERY_OP),
+             ("paper_five_ops", 0, 2, B.FP_BOUNDARY_PAPER_OPS), ("layer_level", 0, 2, B.FP_BOUNDARY_LAYER),
+             ("chunk_512", 512, 2, 0), ("chunk_2048", 2048, 2, 0), ("chunk_8192", 8192, 2, 0),
+             ("op_level_in_chunk_4096", 4096, 2, B.FP_BOUNDARY_EVERY_OP),
+             ("op_level_in_chunk_8192", 8192, 2, B.FP_BOUNDARY_EVERY_OP),
+             ("op_level_in_chunk_16384", 16384, 2, B.FP_BOUNDARY_EVERY_OP)]
+    for name, chunk, ahead, mask in modes:
+        pool = E.MixedPool(model, mask or B.FP_BOUNDARY_EVERY_OP, launch_ahead=ahead,
+                           chunk_op_mask=mask if chunk else 0)
         state = {"longs": 0, "stop": False}
 
         def reissue(req, state=state):

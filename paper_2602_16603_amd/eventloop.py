@@ -212,39 +212,57 @@ class PrefillPool:
 
 
 class ChunkedPrefillTask:
-    """Fixed chunked prefill of one prompt (the baseline of Section 3.1 / Fig. 2): the prompt is
-    run `chunk` tokens at a time through the whole stack, every chunk attending to the KV its
-    predecessors left in the paged cache; the scheduler can take the GPU only between chunks.
-    Host logic only -- each chunk is an ordinary task of the library with no operator-level
-    checks."""
+    """Chunked prefill of one prompt: the prompt is run `chunk` tokens at a time through the
+    whole stack, every chunk attending to the KV its predecessors left in the paged cache.
 
-    def __init__(self, model, hidden, n_tokens: int, chunk: int):
+    op_mask == 0: the fixed-chunk baseline of Section 3.1 / Fig. 2 -- the scheduler can take the
+    GPU only between chunks.  op_mask != 0: operator-level preemption combined with chunking
+    (Section 6.5, "FlowPrefill with chunked prefill"): every chunk is an operator-preemptible
+    task, so a request is honoured at the next operator boundary inside the running chunk, and
+    chunking only caps how long the longest operator can be.  Host logic only."""
+
+    def __init__(self, model, hidden, n_tokens: int, chunk: int, op_mask: int = 0, launch_ahead: int = 2):
         from . import binding as B
         self._B = B
         self.model, self.hidden, self.n, self.chunk = model, hidden, n_tokens, chunk
+        self.op_mask, self.launch_ahead = op_mask, launch_ahead
         self.blocks = B.fp_kv_alloc(model.handle, (n_tokens + 15) // 16)
         self.table = self.blocks.reshape(1, -1)
         self.done_tokens = 0
         self.cond = threading.Condition()
         self.signal = False
         self.parked = False
+        self.parked_inside = False          # parked at an operator boundary inside self.current
         self.finished = False
+        self.current = None                 # the chunk's task while it exists
 
     def run(self) -> int:
         B = self._B
         while self.done_tokens < self.n:
-            with self.cond:                        # chunk boundary: the only place a preempt lands
-                if self.signal:
+            if self.current is None:
+                lo, hi = self.done_tokens, min(self.n, self.done_tokens + self.chunk)
+                with self.cond:                    # chunk boundary
+                    if self.signal:
+                        self.signal = False
+                        self.parked = True
+                        self.cond.notify_all()
+                        return PREEMPTED
+                    task = self.model.begin(self.hidden[lo:hi], [hi - lo], cached=[lo],
+                                            block_tables=self.table, boundary_mask=self.op_mask)
+                    if self.op_mask:
+                        B.fp_prefill_set_launch_ahead(task.handle, self.launch_ahead)
+                    self.current = task
+            status = _advance_or_parked(self.current)
+            with self.cond:
+                if status == PREEMPTED:            # parked at an operator boundary inside the chunk
                     self.signal = False
                     self.parked = True
+                    self.parked_inside = True
                     self.cond.notify_all()
                     return PREEMPTED
-            lo, hi = self.done_tokens, min(self.n, self.done_tokens + self.chunk)
-            task = self.model.begin(self.hidden[lo:hi], [hi - lo], cached=[lo], block_tables=self.table,
-                                    boundary_mask=B.FP_BOUNDARY_NONE)
-            task.run_to_completion()
-            task.end()
-            self.done_tokens = hi
+                self.done_tokens += self.current.lengths[0]
+                self.current.end()
+                self.current = None
         with self.cond:
             self.finished = True
             self.signal = False
@@ -252,17 +270,28 @@ class ChunkedPrefillTask:
         return DONE
 
     def preempt(self) -> int:
+        B = self._B
         with self.cond:
             if not self.finished and not self.parked:
                 self.signal = True
+                if self.op_mask and self.current is not None:
+                    # Non-blocking: sets the running chunk's signal (or parks it if its advance
+                    # has not begun).  Under the lock, so the chunk's task cannot be ended meanwhile.
+                    B.fp_preempt_signal(self.current.handle)
                 self.cond.wait_for(lambda: self.parked or self.finished)
             return DONE if self.finished else PREEMPTED
 
     def resume(self) -> None:
         with self.cond:
             self.parked = False
+            if self.parked_inside:
+                self.parked_inside = False
+                self.current.resume()
 
     def end(self) -> None:
+        if self.current is not None:
+            self.current.end()
+            self.current = None
         if self.blocks is not None:
             self._B.fp_kv_free(self.model.handle, self.blocks)
             self.blocks = None
@@ -271,16 +300,18 @@ class ChunkedPrefillTask:
 class MixedPool:
     """Execution pool for the preemption workload: requests whose payload is a
     (hidden, chunk) pair with chunk > 0 run as fixed chunked prefill, all others as one
-    operator-preemptible task."""
+    operator-preemptible task.  chunk_op_mask != 0 makes the chunks themselves operator-preemptible."""
 
-    def __init__(self, model, boundary_mask: int, launch_ahead: int = 2, short_tokens: int = 2048):
+    def __init__(self, model, boundary_mask: int, launch_ahead: int = 2, short_tokens: int = 2048,
+                 chunk_op_mask: int = 0):
         self.model, self.boundary_mask, self.launch_ahead = model, boundary_mask, launch_ahead
+        self.chunk_op_mask = chunk_op_mask
         self.short_tokens = short_tokens     # requests up to this size run with unbounded launch-ahead
 
     def submit(self, req: Request):
         hidden, chunk = req.payload
         if chunk:
-            return ChunkedPrefillTask(self.model, hidden, req.n_tokens, chunk)
+            return ChunkedPrefillTask(self.model, hidden, req.n_tokens, chunk, self.chunk_op_mask, self.launch_ahead)
         task = self.model.begin(hidden, [req.n_tokens], boundary_mask=self.boundary_mask)
         from . import binding as B
         B.fp_prefill_set_launch_ahead(task.handle, 0 if req.n_tokens <= self.short_tokens else self.launch_ahead)
