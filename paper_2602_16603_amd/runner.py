@@ -84,7 +84,7 @@ class PrefillTask:
         for n in self.lengths:
             self.cu.append(self.cu[-1] + n)
         assert hidden.is_cuda and hidden.dtype == model.torch_dtype and hidden.is_contiguous()
-        assert hidden.shape == (self.cu[-1], model.spec.hidden)
+        assert tuple(hidden.shape) == (self.cu[-1], model.spec.hidden)
         torch.cuda.current_stream().synchronize()   # hidden was produced on torch's stream
         self.handle = B.fp_prefill_begin(model.handle, hidden.data_ptr(), self.cu,
                                          None if cached is None else self.cached, block_tables,
