@@ -355,35 +355,52 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
   // Epilogue.  The MFMAs take the W fragment as their row operand, so each 32x32 accumulator is
   // a block of C^T: lane l holds output row m = l%32 and, per register quad a, the four
   // consecutive columns n = 8a + 4*(l/32) + (0..3).
+  // Each wave stages its block through its own 16 KB of the (now idle) LDS stages so that global
+  // memory sees whole 128-byte row segments (8 full cache lines per instruction) instead of the
+  // 8/16-byte pieces the accumulator layout would give.
+  bf16* region = (wave >> 1) == 0 ? sA0 : (wave >> 1) == 1 ? sA1 : (wave >> 1) == 2 ? sB0 : sB1;
+  region += (wave & 1) * (128 * 64);
   if (EPI != kEpiBf16) {
-    // fp32 residual: one 16-byte read-modify-write per quad.  Split-K partial: a plain 16-byte
-    // store into this split's [M][N] slab of the workspace.
-    float* cf = reinterpret_cast<float*>(Cout) + (EPI == kEpiPartial ? (int64_t)split * M * N : 0);
+    // fp32 residual (read-modify-write) or split-K partial (plain store into this split's
+    // [M][N] slab): two passes of 32 columns, staged as [128 rows][8 chunks of 4 floats], chunk c
+    // of row r at position c ^ ((r>>1)&7).
+    float* stage = reinterpret_cast<float*>(region);
+    float* cf = reinterpret_cast<float*>(Cout) + (EPI == kEpiPartial ? (int64_t)split * M * N : 0) +
+                (int64_t)(m0 + wm * 128) * N + n0 + wn * 64;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m = m0 + wm * 128 + i * 32 + frag_row;
-      if (m >= M) continue;
+    for (int j = 0; j < 2; ++j) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int i = 0; i < 4; ++i) {
+        const int row = i * 32 + frag_row;
+        const int rkey = (row >> 1) & 7;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-          const int n = n0 + wn * 64 + j * 32 + 8 * a + 4 * half;
-          if (n >= N) continue;                     // N is a multiple of 8: quads are all-in or all-out
-          f32x4* c = reinterpret_cast<f32x4*>(cf + (int64_t)m * N + n);
           f32x4 v;
-          if (RESID) v = *c;
 #pragma unroll
-          for (int b = 0; b < 4; ++b) v[b] = RESID ? v[b] + acc[i][j][4 * a + b] : acc[i][j][4 * a + b];
+          for (int b = 0; b < 4; ++b) v[b] = acc[i][j][4 * a + b];
+          *reinterpret_cast<f32x4*>(stage + row * 32 + (((2 * a + half) ^ rkey) << 2)) = v;
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(kWaitLgkm0);   // own wave's LDS writes have landed; no other wave touches the region
+#pragma unroll
+      for (int it = 0; it < 16; ++it) {
+        const int idx = lane + it * 64;
+        const int row = idx >> 3, ch = idx & 7;
+        f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * 32 + ((ch ^ ((row >> 1) & 7)) << 2));
+        if (m0 + wm * 128 + row < M && n0 + wn * 64 + j * 32 + ch * 4 < N) {   // N % 8 == 0: quads all-in or all-out
+          f32x4* c = reinterpret_cast<f32x4*>(cf + (int64_t)row * N + j * 32 + ch * 4);
+          if (RESID) {
+            const f32x4 x = *c;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) v[b] += x[b];
+          }
           *c = v;
         }
       }
     }
   } else {
-    // bf16 output: each wave stages its 128x64 block in its own 16 KB of the (now idle) LDS
-    // stages as [128 rows][8 chunks of 8 bf16], chunk c of row r at position c ^ ((r>>1)&7), then
-    // stores whole 128-byte rows with 16-byte accesses (8 full cache lines per instruction).
-    bf16* region = (wave >> 1) == 0 ? sA0 : (wave >> 1) == 1 ? sA1 : (wave >> 1) == 2 ? sB0 : sB1;
-    region += (wave & 1) * (128 * 64);
+    // bf16 output: staged as [128 rows][8 chunks of 8 bf16], chunk c of row r at position
+    // c ^ ((r>>1)&7), then stored as whole 128-byte rows with 16-byte accesses.
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = i * 32 + frag_row;
