@@ -12,8 +12,13 @@ namespace fp {
 //
 // One workgroup = 8 waves = one (sequence, query tile of 256 rows, query head); each wave owns
 // 32 query rows.  Two waves share a SIMD, so one wave's softmax arithmetic (VALU, exp) overlaps
-// the other's MFMAs.  Keys are consumed 64 at a time (four 16-token cache blocks), staged in LDS,
-// double-buffered.
+// the other's MFMAs.  Keys are consumed 64 at a time (four 16-token cache blocks) from a ring of
+// three LDS stages filled by DMA (buffer_load ... lds): tile t+2 is requested while tile t is
+// being consumed, by waves 0..3 only, after their own P V -- they win MFMA arbitration, finish a
+// tile first and would otherwise idle at the barrier, so the ~500 cycles the eight waves' 32 KB of
+// requests need on the CU's 64 B/clk vector-memory path stay off the critical path.  (Loading
+// through registers at the top of the tile, with the block-table look-up in front, kept every
+// wave in instruction issue for 1500 of 4900 cycles per tile.)
 //
 // The score tile is computed TRANSPOSED, S^T = K Q^T: the MFMA accumulator layout then gives
 // each lane one query column and 16 key rows per 32-key block, so the row maximum and row sum of
@@ -55,6 +60,39 @@ template <int D> __device__ __forceinline__ int k_key_of_lane(int lq) {
 }
 __device__ __forceinline__ int pi_swap23(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
 
+// DMA of one loader wave's share of a 64-key tile: IPW 1 KB instructions each for K and V.  One
+// descriptor per instruction, over exactly the (block, kv head) slab it reads; a block past the
+// end of the sequence gets an empty descriptor, so its rows arrive as zeros.
+// Workgroup barrier without the memory fence of __syncthreads (the fence would wait for the DMA
+// just issued for a later tile); callers wait for exactly the DMA they need before it.
+__device__ __forceinline__ void tile_barrier() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int D, int IPW>
+__device__ __forceinline__ void dma_kv_tile(int j0, int tile, int total, const int32_t* bt,
+                                            bf16* k_head, bf16* v_head, int64_t block_elems,
+                                            const uint32_t (&koff)[IPW], const uint32_t (&voff)[IPW],
+                                            bf16* dK, bf16* dV) {
+  constexpr int IPB = D / 32;                // instructions per 16-token block
+#pragma unroll
+  for (int u = 0; u < IPW; ++u) {
+    const int j = j0 + u;
+    const int lb = tile * 4 + j / IPB;
+    const bool valid = lb * kKvBlock < total;
+    const int64_t blk = valid ? bt[lb] : 0;
+    const int bytes = valid ? kKvBlock * D * 2 : 0;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        __builtin_amdgcn_make_buffer_rsrc(k_head + blk * block_elems, 0, bytes, 0x00020000),
+        (__attribute__((address_space(3))) void*)(dK + j * 512), 16, koff[u], 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        __builtin_amdgcn_make_buffer_rsrc(v_head + blk * block_elems, 0, bytes, 0x00020000),
+        (__attribute__((address_space(3))) void*)(dV + j * 512), 16, voff[u], 0, 0, 0);
+  }
+}
+
 template <int D, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
     const bf16* __restrict__ qkv, const bf16* __restrict__ k_pool, const bf16* __restrict__ v_pool,
@@ -62,20 +100,28 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ cached_lens,
     const int32_t* __restrict__ block_tables, int max_blocks,
     const int32_t* __restrict__ attn_items, float scale_log2) {
-  constexpr int NT = NW * 64;
+  static_assert(NW == 8, "work split assumes 8 waves");
   constexpr int BQW = NW * 32;
   constexpr int CPR = D / 8;                 // 16-byte chunks per key row
-  constexpr int CH = kKvBlock * CPR;         // chunks per 16-token block
-  constexpr int PASSES = 4 * CH / NT;        // per-thread chunks per tile (K and V each)
   constexpr int DB = D / 32;                 // 32-channel blocks of the output
   constexpr int KK = D / 16;                 // MFMA k-steps of the score contraction
-  static_assert(PASSES >= 1 && 4 * CH % NT == 0, "tile loaders need 4*CH to be a multiple of NT");
+  constexpr int NI = D / 8;                  // 1 KB DMA instructions per 64-key tile (K and V each)
+  constexpr int NL = 4;                      // loader waves
+  constexpr int IPW = NI / NL;               // DMA instructions per loader wave (K and V each)
+  constexpr int RPI = 512 / D;               // key rows per K instruction
+  constexpr int IPB = NI / 4;                // instructions per 16-token block
+  constexpr int TILE = kKT * D;              // elements per tile buffer
+  constexpr int kWaitOwnDma = 0x0F70 | (2 * IPW);   // vmcnt(2*IPW): all but the newest tile's DMA
 
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16* sK = reinterpret_cast<bf16*>(smem_raw);   // [2][64*D]
-  bf16* sV = sK + 2 * kKT * D;                    // [2][64*D]
+  __shared__ __attribute__((aligned(1024))) bf16 sK0[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16 sK1[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16 sK2[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16 sV0[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16 sV1[TILE];
+  __shared__ __attribute__((aligned(1024))) bf16 sV2[TILE];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 31, lh = lane >> 5;
   const int group = n_q_heads / n_kv_heads;
   const int w = blockIdx.x;
@@ -96,7 +142,30 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
   const int n_tiles = (kv_len + kKT - 1) / kKT;
   const int64_t width = (int64_t)(n_q_heads + 2 * n_kv_heads) * D;
   const int32_t* bt = block_tables + (int64_t)s * max_blocks;
-  const int64_t pool_layer = (int64_t)layer * kv_num_blocks;
+  const int64_t block_elems = (int64_t)n_kv_heads * kKvBlock * D;           // one block, all kv heads
+  const int64_t head_elems = ((int64_t)layer * kv_num_blocks * n_kv_heads + kvh) * (kKvBlock * D);
+  bf16* const k_head = const_cast<bf16*>(k_pool) + head_elems;              // block 0 of this layer, this kv head
+  bf16* const v_head = const_cast<bf16*>(v_pool) + head_elems;
+  const bool loader = wave < NL;
+
+  // Per-lane source offsets inside one (block, kv head) slab (16 x D elements) for this wave's DMA
+  // instructions.  A DMA instruction writes lane i's 16 bytes at LDS base + 16 i, so the LDS
+  // swizzles are obtained by permuting which 16-byte source chunk each lane fetches.
+  uint32_t koff[IPW], voff[IPW];
+#pragma unroll
+  for (int u = 0; u < IPW; ++u) {
+    const int j = (wave & (NL - 1)) * IPW + u;          // instruction index within the tile
+    const int row = j * RPI + lane / CPR;               // key row of the tile this lane fills
+    const int pch = lane % CPR;
+    const int src = pch ^ k_key_of_lane<D>(pi_swap23(row & 31));
+    koff[u] = (uint32_t)((row % kKvBlock) * D * 2 + src * 16);
+    const int q = (j % IPB) * 64 + lane;                // 16-byte slot inside the block's V slab
+    const int d = q >> 1, hp = q & 1;
+    voff[u] = (uint32_t)((d * 2 + (hp ^ ((d >> 3) & 1))) * 16);
+  }
+  auto dma_tile = [&](int tile, bf16* dK, bf16* dV) {
+    dma_kv_tile<D, IPW>((wave & (NL - 1)) * IPW, tile, total, bt, k_head, v_head, block_elems, koff, voff, dK, dV);
+  };
 
   // ---- query fragments (B operand of S^T = K Q^T), resident for the whole kernel ----
   bf16x8 qf[KK];
@@ -115,62 +184,19 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
   float m_use = -INFINITY;      // exponent reference (raw score units)
   float l_run = 0.f;            // this lane's half of the row sum
 
-  u32x4 rk[PASSES], rv[PASSES];
-  auto load_tile = [&](int tile) {
-#pragma unroll
-    for (int i = 0; i < PASSES; ++i) {
-      const int flat = tid + i * NT;
-      const int c = flat / CH, chunk = flat % CH;
-      const int lb = tile * 4 + c;
-      if (lb * kKvBlock < total) {
-        const int64_t blk = bt[lb];
-        const int64_t base = ((pool_layer + blk) * n_kv_heads + kvh) * (int64_t)(kKvBlock * D);
-        rk[i] = *reinterpret_cast<const u32x4*>(k_pool + base + chunk * 8);
-        rv[i] = *reinterpret_cast<const u32x4*>(v_pool + base + chunk * 8);
-      } else {
-        rk[i] = u32x4{0, 0, 0, 0};
-        rv[i] = u32x4{0, 0, 0, 0};
-      }
-    }
-  };
-  auto store_tile = [&](int buf) {
-    bf16* dK = sK + buf * kKT * D;
-    bf16* dV = sV + buf * kKT * D;
-#pragma unroll
-    for (int i = 0; i < PASSES; ++i) {
-      const int flat = tid + i * NT;
-      const int c = flat / CH, chunk = flat % CH;
-      const int key = chunk / CPR, dch = chunk % CPR;
-      const int row = c * kKvBlock + key;
-      const int swz = k_key_of_lane<D>(pi_swap23(row & 31));
-      *reinterpret_cast<u32x4*>(dK + row * D + ((dch ^ swz) << 3)) = rk[i];
-      const int d = chunk >> 1, half = chunk & 1;
-      const int phys = d * 2 + (half ^ ((d >> 3) & 1));
-      *reinterpret_cast<u32x4*>(dV + c * (D * kKvBlock) + (phys << 3)) = rv[i];
-    }
-  };
-
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
-
   const int wave_q_min = cached + wq0;               // smallest query position of the wave
   const int wave_q_max = cached + wq0 + 31;          // largest
   const int qpos = cached + wq0 + lq;
   const int pi_row = pi_swap23(lq);
   const int k_swz = k_key_of_lane<D>(lq);
   const float lazy_gap = 8.0f / scale_log2;          // 2^8 of head-room, in raw score units
+  const bool wave_valid = wq0 < n_new;
 
-  for (int t = 0; t < n_tiles; ++t) {
-    const int cur = t & 1;
-    if (t + 1 < n_tiles) load_tile(t + 1);
+  // One tile: scores, softmax, P V from stage (cK, cV); the loader waves then start the DMA of
+  // tile t + 2 into (nK, nV), the stage every wave finished reading before the previous barrier.
+  auto tile_step = [&](int t, const bf16* cK, const bf16* cV, bf16* nK, bf16* nV) __attribute__((always_inline)) {
     const int key0 = t * kKT;
-    if (key0 <= wave_q_max && wq0 < n_new) {
-      const bf16* cK = sK + cur * kKT * D;
-      const bf16* cV = sV + cur * kKT * D;
-      // ---- S^T = K Q^T ----  (the eight K fragments of a 32-key block are fetched before the
-      // MFMAs that consume them -- the scheduling fence keeps the compiler from sinking each read
-      // next to its MFMA -- so LDS latency is paid once per block, not once per MFMA)
+    if (key0 <= wave_q_max && wave_valid) {
       f32x16 sacc[2];
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
@@ -186,7 +212,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
         for (int kk = 0; kk < KK; ++kk)
           sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sacc[rb], 0, 0, 0);
       }
-      // ---- online softmax for this lane's query column ----
       if (key0 + kKT - 1 > wave_q_min) {              // tile straddles the diagonal: mask
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
@@ -227,7 +252,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
         pf[c] = __builtin_convertvector(pv, bf16x8);
       }
       l_run += psum;
-      // ---- O^T += V^T P^T ----  (same: the four V fragments of a channel block first)
 #pragma unroll
       for (int i = 0; i < DB; ++i) {
         const int d = i * 32 + lq;
@@ -242,12 +266,31 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
           oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c], pf[c], oacc[i], 0, 0, 0);
       }
     }
-    if (t + 1 < n_tiles) store_tile(cur ^ 1);
-    __syncthreads();
+    if (loader) {
+      if (t + 2 < n_tiles) {
+        dma_tile(t + 2, nK, nV);
+        __builtin_amdgcn_s_waitcnt(kWaitOwnDma);     // tile t+1's DMA (issued a tile ago) has landed
+      } else {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+      }
+    }
+    tile_barrier();
+  };
+
+  if (loader) {
+    dma_tile(0, sK0, sV0);
+    if (1 < n_tiles) dma_tile(1, sK1, sV1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+  }
+  tile_barrier();
+  for (int t = 0; t < n_tiles; t += 3) {
+    tile_step(t, sK0, sV0, sK2, sV2);
+    if (t + 1 < n_tiles) tile_step(t + 1, sK1, sV1, sK0, sV0);
+    if (t + 2 < n_tiles) tile_step(t + 2, sK2, sV2, sK1, sV1);
   }
 
   // ---- normalise, stage through LDS, store rows with 16-byte accesses ----
-  bf16* stage = reinterpret_cast<bf16*>(smem_raw) + wave * (32 * D);
+  bf16* stage = ((wave >> 1) == 0 ? sK0 : (wave >> 1) == 1 ? sK1 : (wave >> 1) == 2 ? sK2 : sV0) + (wave & 1) * (32 * D);
   {
     const float l_tot = xhalf_sum(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
@@ -335,16 +378,9 @@ template <int D>
 static void launch_attn_bf16(const void* qkv, const void* k_pool, const void* v_pool, void* o,
                              const Geometry& g, const BatchMeta& m, int layer, hipStream_t s) {
   constexpr int NW = 8;
-  const size_t smem = (size_t)4 * kKT * D * sizeof(bf16);
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<D, NW>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    attr_set = true;
-  }
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)D);
   dim3 grid((unsigned)((int64_t)m.n_attn_items * g.n_q_heads));
-  attn_bf16_kernel<D, NW><<<grid, NW * 64, smem, s>>>(
+  attn_bf16_kernel<D, NW><<<grid, NW * 64, 0, s>>>(
       (const bf16*)qkv, (const bf16*)k_pool, (const bf16*)v_pool, (bf16*)o, g.n_q_heads,
       g.n_kv_heads, g.kv_num_blocks, layer, m.cu_seqlens, m.cached_lens, m.block_tables,
       m.max_blocks, m.attn_items, scale_log2);
