@@ -195,6 +195,13 @@ void fp_prefill_end(fp_prefill* task);
  *                  overwritten; residual=1: C is fp32 and accumulated into (x += ...).
  *   fp_op_rmsnorm  out[T,d] (storage dtype) = rmsnorm(x[T,d] fp32) * gain[d]
  *   fp_op_silu_mul out[T,F] = silu(gu[:, :F]) * gu[:, F:]
+ *   fp_op_gemm_swiglu  bf16 only: out[M,F] = silu(G) * U with [G | U] = A[M,K] W[2F,K]^T rounded
+ *                  to bf16 (W rows: F gate rows, then F up rows) -- the gate_up projection with
+ *                  the activation fused into its epilogue, the form the prefill path uses for
+ *                  operators 6+7 when the problem fills the chip (the SwiGLU MLP of the operator
+ *                  list in Section 5.1); same bits as fp_op_gemm followed by fp_op_silu_mul.
+ *                  FP_ERR_INVALID for shapes the fused kernel does not take (K % 64, F % 8, fewer
+ *                  than 96 output tiles of 256 x 128): callers then use the two-operator form.
  * FP_ERR_INVALID on misaligned or non-positive sizes (K and N multiples of 8).                   */
 fp_status fp_op_gemm(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
                      int64_t k, int32_t residual, void* hip_stream);
@@ -202,6 +209,8 @@ fp_status fp_op_rmsnorm(int32_t dtype, const void* x_f32, const void* gain, void
                         int64_t t, int64_t d, float eps, void* hip_stream);
 fp_status fp_op_silu_mul(int32_t dtype, const void* gu, void* out, int64_t t, int64_t f,
                          void* hip_stream);
+fp_status fp_op_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t m, int64_t f,
+                            int64_t k, void* hip_stream);
 
 const char* fp_last_error(void);
 const char* fp_version(void);

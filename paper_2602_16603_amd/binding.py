@@ -68,6 +68,7 @@ _SIGS = {
     "fp_op_gemm": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _P]),
     "fp_op_rmsnorm": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_float, _P]),
     "fp_op_silu_mul": (C.c_int, [C.c_int32, _P, _P, C.c_int64, C.c_int64, _P]),
+    "fp_op_gemm_swiglu": (C.c_int, [_P, _P, _P, C.c_int64, C.c_int64, C.c_int64, _P]),
     "fp_last_error": (C.c_char_p, []),
     "fp_version": (C.c_char_p, []),
 }
@@ -241,6 +242,10 @@ def fp_op_rmsnorm(dtype: int, x_f32: int, gain: int, out: int, t: int, d: int, e
 
 def fp_op_silu_mul(dtype: int, gu: int, out: int, t: int, f: int, hip_stream: int = 0) -> None:
     _check(lib.fp_op_silu_mul(dtype, _P(gu), _P(out), t, f, _P(hip_stream)), "fp_op_silu_mul")
+
+
+def fp_op_gemm_swiglu(a: int, w_gate_up: int, out: int, m: int, f: int, k: int, hip_stream: int = 0) -> None:
+    _check(lib.fp_op_gemm_swiglu(_P(a), _P(w_gate_up), _P(out), m, f, k, _P(hip_stream)), "fp_op_gemm_swiglu")
 
 
 def make_shape(spec, dtype: int, kv_num_blocks: int, max_position: int) -> fp_shape:

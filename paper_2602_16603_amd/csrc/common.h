@@ -21,6 +21,10 @@ constexpr int kOpsPerLayer = 9;
 
 // Eight consecutive elements of the storage type, loaded/stored as one vector and handled in
 // fp32 registers.  bf16: one 16-byte access; fp32: two 16-byte accesses.
+// SiLU(gate) * up in fp32: the one formula both the stand-alone operator and the fused GEMM
+// epilogue use, so the two give the same bits.
+__device__ __forceinline__ float silu_mul_f32(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+
 template <typename T> struct Vec8;
 
 template <> struct Vec8<bf16> {

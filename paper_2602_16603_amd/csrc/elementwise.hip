@@ -114,7 +114,7 @@ __global__ __launch_bounds__(256) void silu_mul_kernel(const T* __restrict__ gu,
   f32x8 u = Vec8<T>::load(row + f + c * 8);
   f32x8 o;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = g[e] / (1.0f + __expf(-g[e])) * u[e];
+  for (int e = 0; e < 8; ++e) o[e] = silu_mul_f32(g[e], u[e]);
   Vec8<T>::store(out + r * f + c * 8, o);
 }
 

@@ -201,16 +201,21 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t pp_panel_rsrc(const void* base
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
+// SPLITW (the fused SwiGLU GEMM): a wave's 64 LDS rows of W are 32 gate rows followed by the 32
+// up rows of the same FFN columns; they come through two descriptors (rw, rw2), each shifted so
+// that the per-lane offsets of instructions 0..3 address the right rows of its panel.
+template <bool SPLITW>
 __device__ __forceinline__ void pp_issue_tile(__amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rw,
-                                              int kbyte, const uint32_t (&voff)[8], bf16* sA, bf16* sB,
-                                              int w4) {
+                                              __amdgpu_buffer_rsrc_t rw2, int kbyte,
+                                              const uint32_t (&voff)[8], bf16* sA, bf16* sB, int w4) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int base_row = (w4 * 8 + j) * 8;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(
         ra, (__attribute__((address_space(3))) void*)(sA + base_row * kBK), 16, voff[j], kbyte, 0, 0);
     __builtin_amdgcn_raw_ptr_buffer_load_lds(
-        rw, (__attribute__((address_space(3))) void*)(sB + base_row * kBK), 16, voff[j], kbyte, 0, 0);
+        (SPLITW && j >= 4) ? rw2 : rw, (__attribute__((address_space(3))) void*)(sB + base_row * kBK), 16,
+        voff[SPLITW ? (j & 3) : j], kbyte, 0, 0);
   }
 }
 
@@ -233,10 +238,11 @@ __device__ __forceinline__ void pp_read_frags(const bf16* sA, const bf16* sB, in
 // slotted in one per two MFMAs, so the address unit (16 clocks per dwordx4 instruction) never
 // backs up into the wave's in-order issue.  The branches are scalar and keep MFMAs and loads in
 // source order without further scheduling directives.
+template <bool SPLITW>
 __device__ __forceinline__ void pp_mfma_and_loads(const PpFrags& f, f32x16 (&acc)[4][2], bool load,
                                                   __amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rw,
-                                                  int kbyte, const uint32_t (&voff)[8], bf16* sA,
-                                                  bf16* sB, int w4) {
+                                                  __amdgpu_buffer_rsrc_t rw2, int kbyte,
+                                                  const uint32_t (&voff)[8], bf16* sA, bf16* sB, int w4) {
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
@@ -252,7 +258,8 @@ __device__ __forceinline__ void pp_mfma_and_loads(const PpFrags& f, f32x16 (&acc
               ra, (__attribute__((address_space(3))) void*)(sA + base_row * kBK), 16, voff[slot & 7], kbyte, 0, 0);
         else
           __builtin_amdgcn_raw_ptr_buffer_load_lds(
-              rw, (__attribute__((address_space(3))) void*)(sB + base_row * kBK), 16, voff[slot & 7], kbyte, 0, 0);
+              (SPLITW && (slot & 7) >= 4) ? rw2 : rw, (__attribute__((address_space(3))) void*)(sB + base_row * kBK),
+              16, voff[SPLITW ? (slot & 3) : (slot & 7)], kbyte, 0, 0);
       }
     }
 }
@@ -263,9 +270,13 @@ __device__ __forceinline__ void pp_barrier() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// EPI selects the epilogue: bf16 store, fp32 residual read-modify-write, or (split-K) fp32
-// partial sums to a workspace [split][M][N] that splitk_reduce_kernel adds up in a fixed order.
-enum { kEpiBf16 = 0, kEpiResidual = 1, kEpiPartial = 2 };
+// EPI selects the epilogue: bf16 store, fp32 residual read-modify-write, (split-K) fp32 partial
+// sums to a workspace [split][M][N] that splitk_reduce_kernel adds up in a fixed order, or the
+// fused SwiGLU: W is [2N][K] = [gate rows | up rows], the tile covers 128 FFN columns, each
+// wave's two 32-column accumulator blocks are gate and up of the same columns, and the output
+// [M][N] is silu(bf16(gate)) * bf16(up) -- the values, rounding included, that the separate
+// gate_up GEMM + silu_mul operators produce, without the [M][2N] round trip through HBM.
+enum { kEpiBf16 = 0, kEpiResidual = 1, kEpiPartial = 2, kEpiSwiGLU = 3 };
 
 template <int EPI>
 __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restrict__ A,
@@ -274,11 +285,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
                                                            int K, int tiles_m, int tiles_n,
                                                            int kt_per_split) {
   constexpr bool RESID = EPI == kEpiResidual;
-  constexpr int BM = 256, BN = 256;
+  constexpr bool SWIGLU = EPI == kEpiSwiGLU;
+  constexpr int BM = 256, BN = SWIGLU ? 128 : 256;   // output columns per tile
   __shared__ __attribute__((aligned(1024))) bf16 sA0[BM * kBK];
   __shared__ __attribute__((aligned(1024))) bf16 sA1[BM * kBK];
-  __shared__ __attribute__((aligned(1024))) bf16 sB0[BN * kBK];
-  __shared__ __attribute__((aligned(1024))) bf16 sB1[BN * kBK];
+  __shared__ __attribute__((aligned(1024))) bf16 sB0[256 * kBK];
+  __shared__ __attribute__((aligned(1024))) bf16 sB1[256 * kBK];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -307,8 +319,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
   }
   const __amdgpu_buffer_rsrc_t rsrc_a =
       pp_panel_rsrc(A + (int64_t)m0 * K, (uint32_t)(min(BM, M - m0) * K * 2));
-  const __amdgpu_buffer_rsrc_t rsrc_w =
-      pp_panel_rsrc(W + (int64_t)n0 * K, (uint32_t)(min(BN, N - n0) * K * 2));
+  // SwiGLU: gate rows n0 + 32*w4 .. +31 and up rows N + n0 + 32*w4 .. +31 sit at LDS rows 64*w4 ..
+  // of the W stage; shifting each panel's base back by 32*w4 rows makes voff[0..3] (built for LDS
+  // rows 64*w4 + 0..31) address them, and the bound moves with it.
+  const int w_shift = SWIGLU ? 32 * w4 : 0;
+  const uint32_t w_bytes = (uint32_t)((w_shift + min(BN, N - n0)) * K * 2);
+  const __amdgpu_buffer_rsrc_t rsrc_w = pp_panel_rsrc(W + ((int64_t)n0 - w_shift) * K, w_bytes);
+  const __amdgpu_buffer_rsrc_t rsrc_w2 =
+      pp_panel_rsrc(W + ((int64_t)N + n0 - w_shift) * K, SWIGLU ? w_bytes : 0u);
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -319,8 +337,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   if (group == 1) {
-    pp_issue_tile(rsrc_a, rsrc_w, kbyte0, voff, sA0, sB0, w4);
-    if (kt_count > 1) pp_issue_tile(rsrc_a, rsrc_w, kbyte0 + kBK * 2, voff, sA1, sB1, w4);
+    pp_issue_tile<SWIGLU>(rsrc_a, rsrc_w, rsrc_w2, kbyte0, voff, sA0, sB0, w4);
+    if (kt_count > 1) pp_issue_tile<SWIGLU>(rsrc_a, rsrc_w, rsrc_w2, kbyte0 + kBK * 2, voff, sA1, sB1, w4);
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
   }
   pp_barrier();
@@ -340,8 +358,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
     // -- compute phase --
     // Both groups have finished reading this stage (group 0 one phase ago, group 1 just now):
     // group 1 refills it with k-tile t+2 while it computes.
-    pp_mfma_and_loads(f, acc, group == 1 && t + 2 < kt_count, rsrc_a, rsrc_w,
-                      kbyte0 + (t + 2) * kBK * 2, voff, sA, sB, w4);
+    pp_mfma_and_loads<SWIGLU>(f, acc, group == 1 && t + 2 < kt_count, rsrc_a, rsrc_w, rsrc_w2,
+                              kbyte0 + (t + 2) * kBK * 2, voff, sA, sB, w4);
     pp_barrier();
   };
 
@@ -360,7 +378,37 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
   // 8/16-byte pieces the accumulator layout would give.
   bf16* region = (wave >> 1) == 0 ? sA0 : (wave >> 1) == 1 ? sA1 : (wave >> 1) == 2 ? sB0 : sB1;
   region += (wave & 1) * (128 * 64);
-  if (EPI != kEpiBf16) {
+  if (SWIGLU) {
+    // acc[i][0] = gate, acc[i][1] = up for output columns n0 + 32*wn + (0..31).  Staged as
+    // [128 rows][4 chunks of 8 bf16], chunk c of row r at position c ^ ((r>>2)&3), then stored as
+    // 64-byte row segments with 16-byte accesses.
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = i * 32 + frag_row;
+      const int rkey = (row >> 2) & 3;
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        bf16x4 v;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const float g = static_cast<float>(static_cast<bf16>(acc[i][0][4 * a + b]));
+          const float u = static_cast<float>(static_cast<bf16>(acc[i][1][4 * a + b]));
+          v[b] = static_cast<bf16>(silu_mul_f32(g, u));
+        }
+        *reinterpret_cast<bf16x4*>(region + row * 32 + ((a ^ rkey) << 3) + 4 * half) = v;
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);     // own wave's LDS writes have landed; no other wave touches the region
+    bf16* cbase = reinterpret_cast<bf16*>(Cout) + (int64_t)(m0 + wm * 128) * N + n0 + wn * 32;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int idx = lane + it * 64;
+      const int row = idx >> 2, ch = idx & 3;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(region + row * 32 + ((ch ^ ((row >> 2) & 3)) << 3));
+      if (m0 + wm * 128 + row < M && n0 + wn * 32 + ch * 8 < N)
+        *reinterpret_cast<u32x4*>(cbase + (int64_t)row * N + ch * 8) = v;
+    }
+  } else if (EPI != kEpiBf16) {
     // fp32 residual (read-modify-write) or split-K partial (plain store into this split's
     // [M][N] slab): two passes of 32 columns, staged as [128 rows][8 chunks of 4 floats], chunk c
     // of row r at position c ^ ((r>>1)&7).
@@ -462,6 +510,20 @@ static int pp_splits(int64_t m, int64_t n, int64_t k) {
   int s = (int)std::min<int64_t>(16, 256 / tiles);
   while (s > 1 && (k / kBK) / s < 8) --s;
   return s;
+}
+
+bool gemm_swiglu_fusable(int dtype, int64_t m, int64_t f, int64_t k) {
+  if (dtype != 1 || k % kBK != 0 || f % 8 != 0 || m <= 0) return false;
+  const int64_t tiles = ((m + 255) / 256) * ((f + 127) / 128);
+  return tiles >= 96 && pp_splits(m, 2 * f, k) == 1;
+}
+
+void launch_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t m, int64_t f,
+                        int64_t k, hipStream_t s) {
+  const int tiles_m = (int)((m + 255) / 256), tiles_n = (int)((f + 127) / 128);
+  gemm_bf16_pp_kernel<kEpiSwiGLU><<<dim3((unsigned)(tiles_m * tiles_n)), 512, 0, s>>>(
+      (const bf16*)a, (const bf16*)w_gate_up, out, (int)m, (int)f, (int)k, tiles_m, tiles_n,
+      (int)(k / kBK));
 }
 
 size_t gemm_workspace_bytes(int dtype, int64_t m, int64_t n, int64_t k) {

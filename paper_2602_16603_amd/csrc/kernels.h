@@ -50,6 +50,13 @@ void launch_attention(int dtype, const void* qkv, const void* k_pool, const void
 void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
                  int64_t k, int residual, void* workspace, size_t workspace_bytes, hipStream_t s);
 size_t gemm_workspace_bytes(int dtype, int64_t m, int64_t n, int64_t k);
+// Fused gate_up projection + SiLU(gate)*up (bf16): out[m][f] from a[m][k] and w_gate_up[2f][k]
+// (gate rows first), bit-identical to launch_gemm into [m][2f] followed by launch_silu_mul.
+// Only for problems gemm_swiglu_fusable accepts (K % 64 == 0, f % 8 == 0, enough tiles to fill the
+// chip without splitting K).
+bool gemm_swiglu_fusable(int dtype, int64_t m, int64_t f, int64_t k);
+void launch_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t m, int64_t f,
+                        int64_t k, hipStream_t s);
 
 // Gathers positions 0..len-1 of one sequence (block table row `table_dev`, device) of one layer
 // into contiguous k_out/v_out [len, Hkv, D].

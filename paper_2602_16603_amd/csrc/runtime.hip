@@ -86,6 +86,7 @@ struct fp_prefill {
   // carved out of ws:
   float* x = nullptr;
   void *h = nullptr, *qkv = nullptr, *o = nullptr, *gu = nullptr, *act = nullptr;
+  bool swiglu_fused = false;   // op 6 writes act directly (fused epilogue); op 7 then has no work and gu is not allocated
   void* splitk = nullptr;              // split-K partial sums (0 bytes when no GEMM of this task splits)
   size_t splitk_bytes = 0;
   fp::BatchMeta meta{};
@@ -126,8 +127,13 @@ fp_status launch_op(fp_prefill* t, int32_t index) {
       break;
     case 4: fp::launch_gemm(dt, t->o, w.w_o, t->x, T, d, qd, 1, t->splitk, t->splitk_bytes, s); break;
     case 5: fp::launch_rmsnorm(dt, t->x, w.mlp_norm, t->h, T, d, sh.rms_eps, s); break;
-    case 6: fp::launch_gemm(dt, t->h, w.w_gate_up, t->gu, T, 2 * F, d, 0, t->splitk, t->splitk_bytes, s); break;
-    case 7: fp::launch_silu_mul(dt, t->gu, t->act, T, F, s); break;
+    case 6:
+      if (t->swiglu_fused) fp::launch_gemm_swiglu(t->h, w.w_gate_up, t->act, T, F, d, s);
+      else fp::launch_gemm(dt, t->h, w.w_gate_up, t->gu, T, 2 * F, d, 0, t->splitk, t->splitk_bytes, s);
+      break;
+    case 7:
+      if (!t->swiglu_fused) fp::launch_silu_mul(dt, t->gu, t->act, T, F, s);
+      break;
     case 8: fp::launch_gemm(dt, t->act, w.w_down, t->x, T, d, F, 1, t->splitk, t->splitk_bytes, s); break;
   }
   hipError_t e = hipGetLastError();
@@ -392,8 +398,10 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   const size_t Tn = (size_t)std::max(T, 1);
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  t->swiglu_fused = fp::gemm_swiglu_fusable(sh.dtype, T, (int64_t)F, (int64_t)d);
   const size_t o_x = carve(Tn * d * 4), o_h = carve(Tn * d * e), o_qkv = carve(Tn * W * e),
-               o_o = carve(Tn * qd * e), o_gu = carve(Tn * 2 * F * e), o_act = carve(Tn * F * e);
+               o_o = carve(Tn * qd * e), o_gu = carve(t->swiglu_fused ? 0 : Tn * 2 * F * e),
+               o_act = carve(Tn * F * e);
   const size_t sk_bytes = std::max(
       std::max(fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)W, (int64_t)d), fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)d, (int64_t)qd)),
       std::max(fp::gemm_workspace_bytes(sh.dtype, T, 2 * (int64_t)F, (int64_t)d), fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)d, (int64_t)F)));
@@ -659,6 +667,19 @@ fp_status fp_op_gemm(int32_t dtype, const void* a, const void* w, void* c, int64
   fp::launch_gemm(dtype, a, w, c, m, n, k, residual, nullptr, 0, reinterpret_cast<hipStream_t>(hip_stream));
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? FP_OK : fail(FP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(e));
+}
+
+fp_status fp_op_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t m, int64_t f,
+                            int64_t k, void* hip_stream) {
+  if (!a || !w_gate_up || !out || m <= 0 || f <= 0 || k <= 0 || m > INT32_MAX || 2 * f > INT32_MAX ||
+      k > INT32_MAX)
+    return fail(FP_ERR_INVALID, "fp_op_gemm_swiglu: bad size");
+  if (!fp::gemm_swiglu_fusable(FP_DTYPE_BF16, m, f, k))
+    return fail(FP_ERR_INVALID, "fp_op_gemm_swiglu: shape not handled by the fused kernel "
+                                "(needs K %% 64 == 0, F %% 8 == 0 and at least 96 output tiles)");
+  fp::launch_gemm_swiglu(a, w_gate_up, out, m, f, k, reinterpret_cast<hipStream_t>(hip_stream));
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? FP_OK : fail(FP_ERR_DEVICE, "gemm_swiglu launch: %s", hipGetErrorString(e));
 }
 
 fp_status fp_op_rmsnorm(int32_t dtype, const void* x_f32, const void* gain, void* out, int64_t t,

@@ -82,6 +82,35 @@ def test_silu_mul_matches_definition(name, t, f):
     assert max_rel_err(out, ref) <= TOL[name]
 
 
+@pytest.mark.parametrize("m,f,k", [(8192, 14336, 4096), (1000, 14336, 4096), (3000, 1000, 256), (700, 27648, 5120)])
+def test_fused_gate_up_swiglu_equals_the_two_operators(m, f, k):
+    """The gate_up GEMM with SiLU(gate)*up in its epilogue gives the bits of the GEMM followed by
+    the stand-alone silu_mul (ragged M, an FFN width that is not a multiple of the 128-column
+    tile, both 8B and 32B shapes), and both agree with the definition."""
+    B = _binding()
+    a = I.normal_tensor((m, k), 1.0, 40, torch.bfloat16, "cuda")
+    w = I.normal_tensor((2 * f, k), 0.02, 41, torch.bfloat16, "cuda")
+    gu = torch.empty((m, 2 * f), dtype=torch.bfloat16, device="cuda")
+    two = torch.empty((m, f), dtype=torch.bfloat16, device="cuda")
+    fused = torch.full((m, f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    torch.cuda.synchronize()
+    B.fp_op_gemm(1, a.data_ptr(), w.data_ptr(), gu.data_ptr(), m, 2 * f, k, False)
+    B.fp_op_silu_mul(1, gu.data_ptr(), two.data_ptr(), m, f)
+    B.fp_op_gemm_swiglu(a.data_ptr(), w.data_ptr(), fused.data_ptr(), m, f, k)
+    torch.cuda.synchronize()
+    assert torch.equal(fused, two)
+    rows = torch.tensor(sorted({0, 1, 255, 256, m // 2, m - 1}))
+    ref = O.silu_mul(O.linear(a[rows].cpu().double(), w.cpu().double()))
+    assert max_rel_err(fused[rows], ref) <= TOL["bf16"]
+
+
+def test_fused_swiglu_rejects_small_problems():
+    B = _binding()
+    a = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.FlowPrefillError):
+        B.fp_op_gemm_swiglu(a.data_ptr(), a.data_ptr(), a.data_ptr(), 16, 64, 64)
+
+
 def test_bad_sizes_are_rejected_not_launched():
     B = _binding()
     a = torch.zeros(64, device="cuda")
