@@ -212,6 +212,56 @@ fp_status fp_op_silu_mul(int32_t dtype, const void* gu, void* out, int64_t t, in
 fp_status fp_op_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t m, int64_t f,
                             int64_t k, void* hip_stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Event-driven scheduler (Section 5.2): S-EDF priority (Eq. (3)), SLO-aware batching
+ * (Algorithm 1) and the scheduling round of Algorithm 2.  Host-only bookkeeping: it decides which
+ * commands (preempt / submit / resume) the caller should issue to the execution pool; it never
+ * touches the GPU.  Times are seconds on any one monotonic clock of the caller's choosing.
+ *
+ *   fp_sched_create   token_budget = G of Algorithm 1.  ttft_coef[0..n_coef-1] (host): the
+ *                     offline-fitted polynomial of Section 6.3, predicted TTFT in seconds of an
+ *                     execution of n tokens = sum_i coef[i] * n^i.  policy: FP_SCHED_SEDF
+ *                     (Eq. (3)), FP_SCHED_EDF (1/deadline: the chunked-prefill + EDF baseline of
+ *                     Section 6.1) or FP_SCHED_FCFS (arrival order, never preempts).  batching != 0
+ *                     enables Algorithm 1.
+ *   fp_sched_arrive   a new request joins the waiting queue Q_w; deadline = arrival + ttft_slo.
+ *   fp_sched_complete the running execution E (batch head `head_id` and every request batched
+ *                     under it) has finished.  FP_ERR_STATE if head_id is not the running one.
+ *   fp_sched_round    one iteration of Algorithm 2's loop at time `now` (call it after every
+ *                     arrival or completion event).  On return *decision says what to do, in this
+ *                     order: if preempt_id >= 0 preempt that execution (it moves to Q_p); then
+ *                     action FP_SCHED_SUBMIT: start one execution for the n_batch requests
+ *                     batch_ids[] (head first; they leave Q_w), or FP_SCHED_RESUME: resume
+ *                     head_id (it leaves Q_p), or FP_SCHED_NONE.  The state already reflects the
+ *                     decision when the call returns.  At most FP_SCHED_MAX_BATCH requests are
+ *                     batched.
+ *   fp_sched_predict  the polynomial's value for n tokens.
+ * Readings of the paper: sgn(0) = +1; equal priorities are ordered by earlier arrival, then
+ * smaller id; the running execution is not a batching candidate; Algorithm 1 scans all
+ * candidates in priority order with the strict comparisons as printed; a preempted request's
+ * estimate is the polynomial at its full token count.
+ * Not thread-safe: one scheduler thread, as in the paper.                                       */
+typedef struct fp_sched fp_sched;
+enum { FP_SCHED_SEDF = 0, FP_SCHED_EDF = 1, FP_SCHED_FCFS = 2 };
+enum { FP_SCHED_NONE = 0, FP_SCHED_SUBMIT = 1, FP_SCHED_RESUME = 2 };
+enum { FP_SCHED_MAX_BATCH = 64 };
+typedef struct {
+  int64_t preempt_id;                      /* -1: nothing to preempt                            */
+  int32_t action;                          /* FP_SCHED_NONE / _SUBMIT / _RESUME                 */
+  int32_t n_batch;                         /* number of ids in batch_ids (SUBMIT only)          */
+  int64_t head_id;                         /* the execution that runs next (-1 if NONE)         */
+  int64_t batch_ids[FP_SCHED_MAX_BATCH];
+} fp_sched_decision;
+
+fp_status fp_sched_create(int64_t token_budget, const double* ttft_coef, int32_t n_coef,
+                          int32_t policy, int32_t batching, fp_sched** out);
+void fp_sched_destroy(fp_sched* sched);
+fp_status fp_sched_arrive(fp_sched* sched, int64_t id, int64_t n_tokens, double arrival,
+                          double ttft_slo);
+fp_status fp_sched_complete(fp_sched* sched, int64_t head_id);
+fp_status fp_sched_round(fp_sched* sched, double now, fp_sched_decision* decision);
+double fp_sched_predict(const fp_sched* sched, int64_t n_tokens);
+
 const char* fp_last_error(void);
 const char* fp_version(void);
 

@@ -69,6 +69,12 @@ _SIGS = {
     "fp_op_rmsnorm": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_float, _P]),
     "fp_op_silu_mul": (C.c_int, [C.c_int32, _P, _P, C.c_int64, C.c_int64, _P]),
     "fp_op_gemm_swiglu": (C.c_int, [_P, _P, _P, C.c_int64, C.c_int64, C.c_int64, _P]),
+    "fp_sched_create": (C.c_int, [C.c_int64, C.POINTER(C.c_double), C.c_int32, C.c_int32, C.c_int32, C.POINTER(_P)]),
+    "fp_sched_destroy": (None, [_P]),
+    "fp_sched_arrive": (C.c_int, [_P, C.c_int64, C.c_int64, C.c_double, C.c_double]),
+    "fp_sched_complete": (C.c_int, [_P, C.c_int64]),
+    "fp_sched_round": (C.c_int, [_P, C.c_double, _P]),
+    "fp_sched_predict": (C.c_double, [_P, C.c_int64]),
     "fp_last_error": (C.c_char_p, []),
     "fp_version": (C.c_char_p, []),
 }
@@ -252,3 +258,47 @@ def make_shape(spec, dtype: int, kv_num_blocks: int, max_position: int) -> fp_sh
     """fp_shape from an inputs.ShapeSpec-like object (plain attribute copy)."""
     return fp_shape(spec.n_layers, spec.hidden, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
                     spec.ffn, spec.rms_eps, spec.rope_theta, dtype, 16, kv_num_blocks, max_position)
+
+
+# ---- event-driven scheduler (host-only) ----
+FP_SCHED_SEDF, FP_SCHED_EDF, FP_SCHED_FCFS = 0, 1, 2
+FP_SCHED_NONE, FP_SCHED_SUBMIT, FP_SCHED_RESUME = 0, 1, 2
+FP_SCHED_MAX_BATCH = 64
+
+
+class SchedDecision(C.Structure):
+    _fields_ = [("preempt_id", C.c_int64), ("action", C.c_int32), ("n_batch", C.c_int32),
+                ("head_id", C.c_int64), ("batch_ids", C.c_int64 * FP_SCHED_MAX_BATCH)]
+
+
+def fp_sched_create(token_budget: int, ttft_coef, policy: int = FP_SCHED_SEDF, batching: bool = True) -> int:
+    coef = (C.c_double * len(ttft_coef))(*[float(c) for c in ttft_coef])
+    out = _P()
+    _check(lib.fp_sched_create(int(token_budget), coef, len(ttft_coef), policy, int(batching), C.byref(out)),
+           "fp_sched_create")
+    return out.value
+
+
+def fp_sched_destroy(sched: int) -> None:
+    lib.fp_sched_destroy(_P(sched))
+
+
+def fp_sched_arrive(sched: int, id: int, n_tokens: int, arrival: float, ttft_slo: float) -> None:
+    _check(lib.fp_sched_arrive(_P(sched), id, n_tokens, arrival, ttft_slo), "fp_sched_arrive")
+
+
+def fp_sched_complete(sched: int, head_id: int) -> None:
+    _check(lib.fp_sched_complete(_P(sched), head_id), "fp_sched_complete")
+
+
+def fp_sched_round(sched: int, now: float):
+    """-> (preempt_id or None, action, head_id or None, [batch ids])"""
+    d = SchedDecision()
+    _check(lib.fp_sched_round(_P(sched), now, C.byref(d)), "fp_sched_round")
+    return (None if d.preempt_id < 0 else d.preempt_id, d.action, None if d.head_id < 0 else d.head_id,
+            [d.batch_ids[i] for i in range(d.n_batch)])
+
+
+def fp_sched_predict(sched: int, n_tokens: int) -> float:
+    return lib.fp_sched_predict(_P(sched), n_tokens)
+

@@ -64,4 +64,7 @@ void launch_kv_gather(int dtype, const void* k_pool, const void* v_pool, void* k
                       int len, const Geometry& g, int layer, const int32_t* table_dev,
                       hipStream_t s);
 
+// Sets the calling thread's fp_last_error() text (for translation units other than the runtime).
+void set_last_error(const char* message);
+
 }  // namespace fp

@@ -49,6 +49,14 @@ fp_status fail(fp_status code, const char* fmt, ...) {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+}  // namespace
+
+namespace fp {
+void set_last_error(const char* message) { g_last_error = message; }
+}  // namespace fp
+
+namespace {
+
 struct Workspace {
   void* base = nullptr;
   size_t bytes = 0;
