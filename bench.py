@@ -152,6 +152,81 @@ def preemption_workload(seconds: float, seed: int = 4):
     return result
 
 
+def slo_workload(seconds: float, points, seed: int = 6, token_budget: int = 4096):
+    """Multi-SLO serving on the 32-layer 8B shape (Section 6.2's experiment on a synthetic stand-in
+    for its trace): Poisson arrivals of the four request classes of Table 1 with the TTFT SLOs of
+    Table 2, scheduled by the native event-driven scheduler.  Systems compared: S-EDF + SLO-aware
+    batching + operator-level preemption (the paper's system), the same without batching, EDF over
+    fixed chunked prefill with chunk 2048 / 8192 (the CP2K / CP8K baselines) and FCFS without
+    preemption.  TTFT = arrival -> end of the request's prefill; SLO attainment = share of the
+    requests that arrived in the window whose TTFT met their SLO (unfinished ones count as missed)."""
+    import numpy as np
+    import torch
+    from paper_2602_16603_amd import binding as B, eventloop as E, inputs as I, runner as R
+
+    spec = I.CONFIGS["cfg4"]["shape"]
+    max_n = 32768
+    weights = I.make_weights(spec, seed, torch.bfloat16, "cuda")
+    model = R.PrefillModel(spec, weights, B.FP_DTYPE_BF16, kv_num_blocks=(1 << 20) // 16, max_position=max_n)
+    buf = I.make_hidden(max_n, spec.hidden, seed, torch.bfloat16, "cuda")
+
+    # Offline TTFT profile -> polynomial (Section 6.3): second-order fit of prefill time over token count.
+    prof_n, prof_t = [256, 1024, 4096, 8192, 16384], []
+    for n in prof_n:
+        best = None
+        for _ in range(2):
+            task = model.begin(buf[:n], [n])
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            task.run_to_completion()
+            dt = time.perf_counter() - t0
+            task.end()
+            best = dt if best is None else min(best, dt)
+        prof_t.append(best)
+    coef = [float(c) for c in np.polyfit(np.asarray(prof_n, dtype=np.float64), np.asarray(prof_t), 2)[::-1]]
+    result = {"workload": f"{spec.n_layers}-layer 8B shape; request classes and shares of Table 1, TTFT SLOs of "
+                          f"Table 2 (Llama3-8B row); Poisson arrivals for {seconds:g} s per point; token budget G = {token_budget}",
+              "ttft_fit_seconds": {"coef_c0_c1_c2": coef, "profile_tokens": prof_n,
+                                   "profile_seconds": [round(t, 5) for t in prof_t]},
+              "rates": {}}
+    systems = [("s_edf_batching_op_level", B.FP_SCHED_SEDF, True, 0), ("s_edf_op_level", B.FP_SCHED_SEDF, False, 0),
+               ("edf_chunk_2048", B.FP_SCHED_EDF, False, 2048), ("edf_chunk_8192", B.FP_SCHED_EDF, False, 8192),
+               ("fcfs", B.FP_SCHED_FCFS, False, 0)]
+    for rate, slo_scale in points:
+        trace = I.multi_slo_trace(rate, seconds, seed + int(rate * 100), slo_scale=slo_scale)
+        point = {"requests": len(trace), "tokens": sum(t[1] for t in trace)}
+        for name, policy, batching, chunk in systems:
+            pool = E.BatchPool(model, B.FP_BOUNDARY_EVERY_OP, chunk=chunk)
+            loop = E.SloEventLoop(pool, token_budget, coef, policy, batching)
+            reqs = [E.SloRequest(i, n, slo, t, buf[:n], kind) for i, n, t, slo, kind in trace]
+            t_start = time.perf_counter()
+            E.feed_slo_arrivals(loop, reqs)
+            while len(loop.finished) < len(reqs) and time.perf_counter() - t_start < seconds + 20.0:
+                loop.step(0.05)
+            elapsed = time.perf_counter() - t_start
+            met = {r.id for r in loop.finished if r.t_finished - r.t_arrived <= r.slo}
+            per_class = {}
+            for kind in sorted({t[4] for t in trace}):
+                ids = [t[0] for t in trace if t[4] == kind]
+                per_class[kind] = round(sum(1 for i in ids if i in met) / len(ids), 4)
+            text_ttft = [(r.t_finished - r.t_arrived) * 1e3 for r in loop.finished if r.kind == "text"]
+            lat = [x * 1e3 for x in loop.preempt_latency_s]
+            point[name] = {"slo_attainment": round(len(met) / max(1, len(trace)), 4), "per_class": per_class,
+                           "finished": len(loop.finished), "elapsed_s": round(elapsed, 2),
+                           "text_ttft_ms": {"p50": round(percentile(text_ttft, 0.5) or 0, 1),
+                                            "p99": round(percentile(text_ttft, 0.99) or 0, 1)},
+                           "rounds": loop.rounds, "commands": dict(loop.commands),
+                           "mean_batch": round(statistics.fmean(loop.batch_sizes), 2) if loop.batch_sizes else 0,
+                           "blocking_ms_p99": round(percentile(lat, 0.99) or 0, 2)}
+            loop.close()
+            torch.cuda.synchronize()
+            print(f"[slo] {rate:g}/s x{slo_scale:g} {name}: attainment {point[name]['slo_attainment']}, "
+                  f"{elapsed:.1f} s", file=sys.stderr, flush=True)
+        result["rates"][f"{rate:g}/s, SLO x{slo_scale:g}"] = point
+    model.close()
+    return result
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -160,6 +235,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--config", default="cfg2", help="cfg2 (default); other names are for exploration")
     ap.add_argument("--layers", type=int, default=0, help="override layer count (exploration only)")
+    ap.add_argument("--slo-seconds", type=float, default=4.0,
+                    help="arrival window of each (system, rate) point of the multi-SLO scheduling workload; 0 skips it")
+    ap.add_argument("--slo-points", default="16:1,32:1,24:0.2",
+                    help="rate:slo_scale points of that workload (requests per second : factor on Table 2's SLOs)")
     ap.add_argument("--preempt-seconds", type=float, default=2.0,
                     help="length of each mode of the preemption-latency workload (cfg4); 0 skips it")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -273,6 +352,9 @@ def main() -> int:
     torch.cuda.empty_cache()
     if args.preempt_seconds > 0 and args.config == "cfg2" and not args.layers:
         out["preemption"] = preemption_workload(args.preempt_seconds)
+    if args.slo_seconds > 0 and args.config == "cfg2" and not args.layers:
+        out["slo_scheduling"] = slo_workload(
+            args.slo_seconds, [tuple(float(v) for v in x.split(":")) for x in args.slo_points.split(",")])
     print(json.dumps(out))
     return 0
 

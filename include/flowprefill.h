@@ -227,6 +227,9 @@ fp_status fp_op_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int
  *   fp_sched_arrive   a new request joins the waiting queue Q_w; deadline = arrival + ttft_slo.
  *   fp_sched_complete the running execution E (batch head `head_id` and every request batched
  *                     under it) has finished.  FP_ERR_STATE if head_id is not the running one.
+ *   fp_sched_retire   a preempted execution turned out to be finished (fp_preempt returned
+ *                     FP_DONE: the command raced with completion); it leaves Q_p.  FP_ERR_STATE if
+ *                     `id` is not in the preempted queue.
  *   fp_sched_round    one iteration of Algorithm 2's loop at time `now` (call it after every
  *                     arrival or completion event).  On return *decision says what to do, in this
  *                     order: if preempt_id >= 0 preempt that execution (it moves to Q_p); then
@@ -259,6 +262,7 @@ void fp_sched_destroy(fp_sched* sched);
 fp_status fp_sched_arrive(fp_sched* sched, int64_t id, int64_t n_tokens, double arrival,
                           double ttft_slo);
 fp_status fp_sched_complete(fp_sched* sched, int64_t head_id);
+fp_status fp_sched_retire(fp_sched* sched, int64_t id);
 fp_status fp_sched_round(fp_sched* sched, double now, fp_sched_decision* decision);
 double fp_sched_predict(const fp_sched* sched, int64_t n_tokens);
 

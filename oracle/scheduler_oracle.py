@@ -21,8 +21,9 @@ budget).  Readings where the paper is silent or inconsistent:
 
 Pinned (tests/test_scheduler_oracle.py) by: the paper's two-request walk-through (Section 5.2,
 "An illustrated example"), the ordering Eq. (3) is described to give (earliest deadline among
-non-negative slack first; every negative-slack request behind every non-negative one), brute
-force over all subsets for Algorithm 1's admission rule on tiny inputs, the textbook property
+non-negative slack first; every negative-slack request behind every non-negative one), the closed
+form Algorithm 1 has for equal-sized candidates under a linear latency model, its behaviour on a
+misfit and at equality of both comparisons, the textbook property
 that preemptive EDF meets every deadline of a feasible single-machine instance (S-EDF equals
 EDF while all slacks are non-negative), and the bound "at most two scheduling rounds per request"
 of Section 6.3.
@@ -105,6 +106,15 @@ class Scheduler:
         assert self.E is r
         r.state = FINISHED
         self.E = None
+        return list(r.members)
+
+    def retire(self, id: int) -> List[int]:
+        """A preempted execution turned out to have finished before it reached a boundary (the
+        preempt command raced with its completion): it leaves Q_p for good."""
+        r = self.reqs[id]
+        assert r.state == PREEMPTED
+        self.Q_p.remove(r)
+        r.state = FINISHED
         return list(r.members)
 
     # -- one scheduling round -----------------------------------------------------------------

@@ -73,6 +73,7 @@ _SIGS = {
     "fp_sched_destroy": (None, [_P]),
     "fp_sched_arrive": (C.c_int, [_P, C.c_int64, C.c_int64, C.c_double, C.c_double]),
     "fp_sched_complete": (C.c_int, [_P, C.c_int64]),
+    "fp_sched_retire": (C.c_int, [_P, C.c_int64]),
     "fp_sched_round": (C.c_int, [_P, C.c_double, _P]),
     "fp_sched_predict": (C.c_double, [_P, C.c_int64]),
     "fp_last_error": (C.c_char_p, []),
@@ -289,6 +290,10 @@ def fp_sched_arrive(sched: int, id: int, n_tokens: int, arrival: float, ttft_slo
 
 def fp_sched_complete(sched: int, head_id: int) -> None:
     _check(lib.fp_sched_complete(_P(sched), head_id), "fp_sched_complete")
+
+
+def fp_sched_retire(sched: int, id: int) -> None:
+    _check(lib.fp_sched_retire(_P(sched), id), "fp_sched_retire")
 
 
 def fp_sched_round(sched: int, now: float):

@@ -91,6 +91,15 @@ fp_status fp_sched_complete(fp_sched* sched, int64_t head_id) {
   return FP_OK;
 }
 
+fp_status fp_sched_retire(fp_sched* sched, int64_t id) {
+  if (!sched) return sched_fail(FP_ERR_INVALID, "fp_sched_retire: null scheduler");
+  auto it = sched->live.find(id);
+  if (it == sched->live.end() || it->second.state != kPreempted)
+    return sched_fail(FP_ERR_STATE, "fp_sched_retire: that execution is not in the preempted queue");
+  sched->live.erase(it);
+  return FP_OK;
+}
+
 fp_status fp_sched_round(fp_sched* sched, double now, fp_sched_decision* d) {
   if (!sched || !d) return sched_fail(FP_ERR_INVALID, "fp_sched_round: null argument");
   d->preempt_id = -1;

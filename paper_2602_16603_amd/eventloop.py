@@ -330,3 +330,177 @@ class MixedPool:
 
     def finish(self, task) -> None:
         task.end()
+
+
+# ---------------------------------------------------------------------------------------------
+# Event loop under the native scheduler (fp_sched_*): S-EDF priority, SLO-aware batching,
+# Algorithm 2's round after every arrival and completion event.
+# ---------------------------------------------------------------------------------------------
+@dataclass
+class SloRequest:
+    id: int
+    n_tokens: int
+    slo: float                          # TTFT SLO in seconds
+    arrival: float                      # seconds from the start of the run
+    hidden: Any = None                  # [n_tokens, d] device tensor (or a view of a shared one)
+    kind: str = ""
+    t_arrived: float = 0.0
+    t_finished: float = 0.0
+
+
+class SloEventLoop:
+    """Drives `pool` with the decisions of the native scheduler.  pool must provide
+    submit(list of SloRequest) -> handle, run(handle) -> DONE | PREEMPTED (blocking),
+    preempt(handle) -> PREEMPTED | DONE (blocking until acknowledged), resume(handle),
+    finish(handle).  One execution = one batch head and the requests batched under it."""
+
+    def __init__(self, pool, token_budget: int, ttft_coef, policy: int, batching: bool):
+        from . import binding as B
+        self._B = B
+        self.pool = pool
+        self.sched = B.fp_sched_create(token_budget, ttft_coef, policy, batching)
+        self.events: "queue.Queue[Tuple[str, Any]]" = queue.Queue()
+        self.jobs: "queue.Queue[Optional[int]]" = queue.Queue()
+        self.requests = {}                   # id -> SloRequest, everything seen so far
+        self.handles = {}                    # head id -> execution handle
+        self.members = {}                    # head id -> [SloRequest]
+        self.running: Optional[int] = None
+        self.finished: List[SloRequest] = []
+        self.rounds = 0
+        self.commands = {"submit": 0, "preempt": 0, "resume": 0}
+        self.batch_sizes: List[int] = []
+        self.preempt_latency_s: List[float] = []
+        self._retired = set()
+        self.t0 = time.perf_counter()
+        self._worker = threading.Thread(target=self._work, daemon=True)
+        self._worker.start()
+
+    def now(self) -> float:
+        return time.perf_counter() - self.t0
+
+    def _work(self) -> None:
+        while True:
+            head = self.jobs.get()
+            if head is None:
+                return
+            if self.pool.run(self.handles[head]) == DONE:
+                self.events.put(("completion", head))
+
+    def post_arrival(self, req: SloRequest) -> None:
+        req.t_arrived = self.now()
+        self.events.put(("arrival", req))
+
+    def _finish_execution(self, head: int) -> None:
+        t = self.now()
+        self.pool.finish(self.handles.pop(head))
+        for r in self.members.pop(head):
+            r.t_finished = t
+            self.finished.append(r)
+
+    def _round(self, kind: str, what) -> None:
+        B = self._B
+        if kind == "arrival":
+            self.requests[what.id] = what
+            B.fp_sched_arrive(self.sched, what.id, what.n_tokens, what.t_arrived, what.slo)
+        else:
+            if what in self._retired:           # finished while being preempted; already retired
+                self._retired.discard(what)
+                return
+            B.fp_sched_complete(self.sched, what)
+            self._finish_execution(what)
+            self.running = None
+        self.rounds += 1
+        pre, action, head, batch = B.fp_sched_round(self.sched, self.now())
+        if pre is not None:
+            t0 = time.perf_counter()
+            status = self.pool.preempt(self.handles[pre])
+            self.preempt_latency_s.append(time.perf_counter() - t0)
+            self.commands["preempt"] += 1
+            if status == DONE:                  # it finished before the next boundary
+                B.fp_sched_retire(self.sched, pre)
+                self._retired.add(pre)
+                self._finish_execution(pre)
+        if action == B.FP_SCHED_SUBMIT:
+            reqs = [self.requests[i] for i in batch]
+            self.handles[head] = self.pool.submit(reqs)
+            self.members[head] = reqs
+            self.commands["submit"] += 1
+            self.batch_sizes.append(len(reqs))
+        elif action == B.FP_SCHED_RESUME:
+            self.pool.resume(self.handles[head])
+            self.commands["resume"] += 1
+        if action != B.FP_SCHED_NONE:
+            self.running = head
+            self.jobs.put(head)
+
+    def step(self, timeout_s: float) -> bool:
+        try:
+            kind, what = self.events.get(timeout=timeout_s)
+        except queue.Empty:
+            return False
+        self._round(kind, what)
+        return True
+
+    def close(self) -> None:
+        """Stops the executor thread; parks and ends whatever is still queued or running."""
+        if self.running is not None:
+            self.pool.preempt(self.handles[self.running])
+        self.jobs.put(None)
+        self._worker.join(timeout=30)
+        for head in list(self.handles):
+            self.pool.finish(self.handles.pop(head))
+        self._B.fp_sched_destroy(self.sched)
+        self.sched = 0
+
+
+def feed_slo_arrivals(loop: SloEventLoop, requests: List[SloRequest]) -> threading.Thread:
+    t0 = time.perf_counter()
+
+    def feeder():
+        for r in sorted(requests, key=lambda r: r.arrival):
+            delay = t0 + r.arrival - time.perf_counter()
+            if delay > 0:
+                time.sleep(delay)
+            loop.post_arrival(r)
+
+    th = threading.Thread(target=feeder, daemon=True)
+    th.start()
+    return th
+
+
+class BatchPool:
+    """Execution pool for SloEventLoop: a batch of requests becomes one packed variable-length
+    prefill task (operator-preemptible with `boundary_mask`), or -- chunk > 0, single requests
+    only -- fixed chunked prefill whose only boundaries are chunk ends (the CP baselines)."""
+
+    def __init__(self, model, boundary_mask: int, chunk: int = 0, launch_ahead: int = 2,
+                 short_tokens: int = 2048):
+        self.model, self.boundary_mask, self.chunk = model, boundary_mask, chunk
+        self.launch_ahead, self.short_tokens = launch_ahead, short_tokens
+
+    def submit(self, reqs: List[SloRequest]):
+        import torch
+        from . import binding as B
+        total = sum(r.n_tokens for r in reqs)
+        if self.chunk and len(reqs) == 1 and total > self.chunk:
+            return ChunkedPrefillTask(self.model, reqs[0].hidden, total, self.chunk, 0, self.launch_ahead)
+        hidden = reqs[0].hidden if len(reqs) == 1 else torch.cat([r.hidden for r in reqs])
+        task = self.model.begin(hidden, [r.n_tokens for r in reqs],
+                                boundary_mask=self.boundary_mask if not self.chunk else B.FP_BOUNDARY_NONE)
+        B.fp_prefill_set_launch_ahead(task.handle, 0 if total <= self.short_tokens else self.launch_ahead)
+        return task
+
+    def run(self, task) -> int:
+        if isinstance(task, ChunkedPrefillTask):
+            return task.run()
+        return _advance_or_parked(task)
+
+    def preempt(self, task) -> int:
+        return task.preempt()
+
+    def resume(self, task) -> None:
+        task.resume()
+
+    def finish(self, task) -> None:
+        task.end()
+

@@ -146,6 +146,33 @@ def poisson_arrivals(rate_per_s: float, duration_s: float, seed: int, lo: int = 
         out.append((t, int(rng.integers(lo, hi + 1))))
 
 
+# Request classes of the paper's evaluation trace: (name, mean, std of the prompt length in tokens,
+# share of requests) from Table 1 and the Llama3-8B TTFT SLO in seconds from Table 2.
+TRACE_CLASSES = (("text", 590.0, 652.0, 0.68, 0.25), ("image", 532.0, 510.0, 0.08, 0.5),
+                 ("search", 5976.0, 3456.0, 0.20, 4.0), ("file", 6833.0, 5186.0, 0.04, 6.0))
+
+
+def multi_slo_trace(rate_per_s: float, duration_s: float, seed: int, slo_scale: float = 1.0,
+                    max_tokens: int = 32768) -> List[Tuple[int, int, float, float, str]]:
+    """Stand-in for the production trace of Section 6.1 (which does not ship): Poisson arrivals at
+    `rate_per_s` over `duration_s`; each request draws one of the four classes by Table 1's
+    shares, a log-normal prompt length matched to that class's mean and standard deviation
+    (clipped to [16, max_tokens]) and the class's SLO times `slo_scale`.
+    Returns (id, n_tokens, arrival_s, ttft_slo_s, class name), ids in arrival order."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    shares = np.cumsum([c[3] for c in TRACE_CLASSES])
+    t, out = 0.0, []
+    while True:
+        t += float(rng.exponential(1.0 / rate_per_s))
+        if t >= duration_s:
+            return out
+        k = int(np.searchsorted(shares, rng.random() * shares[-1]))
+        name, mean, std, _, slo = TRACE_CLASSES[min(k, len(TRACE_CLASSES) - 1)]
+        sigma2 = float(np.log(1.0 + (std / mean) ** 2))
+        n = float(rng.lognormal(np.log(mean) - sigma2 / 2.0, np.sqrt(sigma2)))
+        out.append((len(out), int(min(max_tokens, max(16, round(n)))), round(t, 6), slo * slo_scale, name))
+
+
 def permuted_block_tables(lengths: Sequence[int], cached: Optional[Sequence[int]],
                           block_tokens: int, pool_blocks: int, seed: int
                           ) -> Tuple[np.ndarray, int]:

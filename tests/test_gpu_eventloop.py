@@ -102,3 +102,68 @@ def test_short_arrivals_preempt_long_prompt_and_results_are_identical(chunk):
     for out in short_out[1:]:
         assert torch.equal(out, short_out[0])                     # identical shorts, identical results
     model.close()
+
+
+def test_scheduler_driven_loop_batches_shorts_and_resumes_long_bit_identically():
+    """The native scheduler (S-EDF + SLO-aware batching) driving the real library: a loose-SLO long
+    prompt is preempted by tight-SLO shorts that arrive together, the shorts run as ONE packed
+    variable-length task (Algorithm 1), the long prompt resumes; the long prompt's result equals
+    an uninterrupted run bit for bit and every batched short equals the same prompt run alone."""
+    from paper_2602_16603_amd.eventloop import BatchPool, SloEventLoop, SloRequest, feed_slo_arrivals
+    B, R = _mods()
+    spec = I.LLAMA3_8B.with_layers(2)
+    long_n = 8192
+    short_ns = [128, 300, 77]
+    weights = I.make_weights(spec, 43, torch.bfloat16, "cuda")
+    model = R.PrefillModel(spec, weights, B.FP_DTYPE_BF16, 4 * (long_n // 16) + 256, long_n)
+    long_h = I.make_hidden(long_n, spec.hidden, 43, torch.bfloat16, "cuda")
+    short_h = [I.make_hidden(n, spec.hidden, 44 + i, torch.bfloat16, "cuda") for i, n in enumerate(short_ns)]
+
+    class KeepPool(BatchPool):
+        def __init__(self, *a, **k):
+            super().__init__(*a, **k)
+            self.kept = []
+
+        def submit(self, reqs):
+            task = super().submit(reqs)
+            self.kept.append(([r.id for r in reqs], task))
+            return task
+
+        def finish(self, task):
+            pass
+
+    def alone(h, n):
+        t = model.begin(h, [n])
+        t.run_to_completion()
+        out = t.hidden()
+        t.end()
+        return out
+
+    want_long = alone(long_h, long_n)
+    want_short = [alone(h, n) for h, n in zip(short_h, short_ns)]
+
+    pool = KeepPool(model, B.FP_BOUNDARY_EVERY_OP)
+    # 1 ms + 10 us per token: the long prompt is predicted at ~83 ms, well inside its 6 s SLO.
+    loop = SloEventLoop(pool, token_budget=4096, ttft_coef=[1e-3, 1e-5], policy=B.FP_SCHED_SEDF, batching=True)
+    reqs = [SloRequest(0, long_n, 6.0, 0.0, long_h, "file")]
+    reqs += [SloRequest(1 + i, n, 0.25, 0.003, h, "text") for i, (h, n) in enumerate(zip(short_h, short_ns))]
+    feed_slo_arrivals(loop, reqs)
+    t0 = time.perf_counter()
+    while len(loop.finished) < len(reqs) and time.perf_counter() - t0 < 60:
+        loop.step(0.05)
+    assert sorted(r.id for r in loop.finished) == [0, 1, 2, 3]
+    assert loop.commands["preempt"] >= 1 and loop.commands["resume"] >= 1
+    batches = {tuple(ids): task for ids, task in pool.kept}
+    assert any(len(ids) > 1 for ids in batches), "the simultaneous shorts were not batched"
+    for ids, task in batches.items():
+        got = task.hidden()
+        if ids == (0,):
+            assert torch.equal(got, want_long)                    # preempted + resumed == uninterrupted
+        else:
+            cu = I.cu_seqlens_of([short_ns[i - 1] for i in ids])
+            for k, i in enumerate(ids):
+                assert torch.equal(got[cu[k]:cu[k + 1]], want_short[i - 1])   # packed == alone
+    loop.close()
+    for _, task in pool.kept:
+        task.end()
+    model.close()

@@ -216,6 +216,24 @@ def test_native_scheduler_takes_the_oracles_decisions(policy, batching, seed):
         assert any(len(e[4]) > 1 for e in log_o)   # the trace does exercise Algorithm 1
 
 
+def test_retire_after_a_preempt_that_raced_with_completion():
+    """B preempts A, but A had already finished: A is retired from Q_p and never resumed; the
+    oracle and the native scheduler agree on what follows."""
+    from paper_2602_16603_amd import binding as B
+    o = S.Scheduler(8192, poly([0.0, 1e-4]), S.POLICY_SEDF, batching=False)
+    n = B.fp_sched_create(8192, [0.0, 1e-4], B.FP_SCHED_SEDF, False)
+    for sch_arrive in (lambda *a: o.arrive(*a), lambda *a: B.fp_sched_arrive(n, *a)):
+        sch_arrive(0, 6000, 0.0, 6.0)
+    assert o.round(0.0).action == "submit" and B.fp_sched_round(n, 0.0)[1] == B.FP_SCHED_SUBMIT
+    o.arrive(1, 500, 0.1, 0.25); B.fp_sched_arrive(n, 1, 500, 0.1, 0.25)
+    d = o.round(0.1); pre, action, head, batch = B.fp_sched_round(n, 0.1)
+    assert d.preempt == 0 == pre and d.head == 1 == head
+    assert o.retire(0) == [0]; B.fp_sched_retire(n, 0)
+    o.complete(1); B.fp_sched_complete(n, 1)
+    assert o.round(0.2).action == "none" and B.fp_sched_round(n, 0.2)[1] == B.FP_SCHED_NONE
+    B.fp_sched_destroy(n)
+
+
 def test_native_scheduler_rejects_bad_calls():
     from paper_2602_16603_amd import binding as B
     with pytest.raises(B.FlowPrefillError):
@@ -227,6 +245,8 @@ def test_native_scheduler_rejects_bad_calls():
     with pytest.raises(B.FlowPrefillError):
         B.fp_sched_complete(s, 7)                  # not running yet
     assert B.fp_sched_round(s, 0.0)[1] == B.FP_SCHED_SUBMIT
+    with pytest.raises(B.FlowPrefillError):
+        B.fp_sched_retire(s, 7)                    # running, not preempted
     B.fp_sched_complete(s, 7)
     assert B.fp_sched_predict(s, 1000) == pytest.approx(1.0)
     B.fp_sched_destroy(s)
