@@ -237,7 +237,7 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override layer count (exploration only)")
     ap.add_argument("--slo-seconds", type=float, default=4.0,
                     help="arrival window of each (system, rate) point of the multi-SLO scheduling workload; 0 skips it")
-    ap.add_argument("--slo-points", default="16:1,32:1,24:0.2",
+    ap.add_argument("--slo-points", default="32:1,24:0.2",
                     help="rate:slo_scale points of that workload (requests per second : factor on Table 2's SLOs)")
     ap.add_argument("--preempt-seconds", type=float, default=2.0,
                     help="length of each mode of the preemption-latency workload (cfg4); 0 skips it")

@@ -9,6 +9,7 @@ import pytest
 import torch
 
 from paper_2602_16603_amd import inputs as I
+from tests.util import TOL, max_rel_err
 from paper_2602_16603_amd.eventloop import EventLoop, MixedPool, Request, feed_arrivals
 
 pytestmark = pytest.mark.gpu
@@ -108,7 +109,8 @@ def test_scheduler_driven_loop_batches_shorts_and_resumes_long_bit_identically()
     """The native scheduler (S-EDF + SLO-aware batching) driving the real library: a loose-SLO long
     prompt is preempted by tight-SLO shorts that arrive together, the shorts run as ONE packed
     variable-length task (Algorithm 1), the long prompt resumes; the long prompt's result equals
-    an uninterrupted run bit for bit and every batched short equals the same prompt run alone."""
+    an uninterrupted run bit for bit and every batched short agrees with the same prompt run alone
+    (to rounding: the split-K factor of the projections depends on the batch's token count)."""
     from paper_2602_16603_amd.eventloop import BatchPool, SloEventLoop, SloRequest, feed_slo_arrivals
     B, R = _mods()
     spec = I.LLAMA3_8B.with_layers(2)
@@ -162,7 +164,7 @@ def test_scheduler_driven_loop_batches_shorts_and_resumes_long_bit_identically()
         else:
             cu = I.cu_seqlens_of([short_ns[i - 1] for i in ids])
             for k, i in enumerate(ids):
-                assert torch.equal(got[cu[k]:cu[k + 1]], want_short[i - 1])   # packed == alone
+                assert max_rel_err(got[cu[k]:cu[k + 1]], want_short[i - 1]) <= TOL["bf16"]   # packed ~ alone
     loop.close()
     for _, task in pool.kept:
         task.end()
