@@ -343,7 +343,7 @@ def main() -> int:
                      "avg_launch_ms": round(dom_avg_ms, 4), "flops_per_launch": dom_flops},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(spec, seed, sample_tokens=min(2048, max(lengths)),
+        out["cpu_baseline"] = cpu_baseline(spec, seed, sample_tokens=min(4096, max(lengths)),
                                            sample_layers=min(2, spec.n_layers))
         out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 2)
         out["cpu_baseline"]["seconds"] = round(out["cpu_baseline"]["seconds"], 2)
