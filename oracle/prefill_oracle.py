@@ -43,8 +43,10 @@ summing to one, single-token and equal-key closed forms, GQA == MHA with repeate
 causality under suffix extension, chunked-with-cache == one-shot, packed == separate sequences,
 RoPE as a textbook 2-D rotation / identity at position 0 / norm preservation / relative-position
 property, RMSNorm scale invariance and unit RMS, SiLU closed-form values, zero-weight residual
-wiring, GEMM against a Python triple loop, and a whole-stack cross-check against a scalar
-per-token pure-Python transcription on a tiny shape.  The paper prints no tensor values, so no
+wiring, GEMM against a Python triple loop, a whole-stack cross-check against a scalar
+per-token pure-Python transcription on a tiny shape, and for the mixture-of-experts FFN: identical
+experts == the dense FFN, top_k == E == the softmax-weighted sum of all experts, a one-hot router
+== that expert alone, a pure-Python loop on tiny inputs, weights summing to one.  The paper prints no tensor values, so no
 number here comes from the paper.
 """
 from __future__ import annotations
@@ -70,6 +72,8 @@ class Shape:
     ffn: int
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
+    n_experts: int = 0            # > 0: mixture-of-experts FFN (Section 7), `ffn` is one expert's width
+    top_k: int = 0
 
     @property
     def q_width(self) -> int:
@@ -91,6 +95,8 @@ class LayerWeights:
     mlp_norm: torch.Tensor
     w_gate_up: torch.Tensor
     w_down: torch.Tensor
+    # Mixture-of-experts layers: w_router [E, d]; w_gate_up [E, 2F, d]; w_down [E, d, F].
+    w_router: Optional[torch.Tensor] = None
 
 
 def _f64(t: torch.Tensor) -> torch.Tensor:
@@ -188,6 +194,47 @@ def silu_mul(gate_up: torch.Tensor) -> torch.Tensor:
 
 
 # --------------------------------------------------------------------------------------------
+# Mixture-of-experts FFN (Section 7, "Mixture-of-Experts (MoE) models": a gated router -- the
+# `gate` operator -- and several expert FFNs -- the `experts` operator).  The paper names the two
+# operators and nothing else; fixed here, as in the MoE family it evaluates: router logits
+# h W_r^T, softmax over ALL experts, the top_k most probable experts per token (ties: lower expert
+# index), their probabilities renormalised to sum to one, every expert a SwiGLU FFN, the layer's
+# output the weighted sum of the selected experts' outputs; no shared expert, no bias.
+# --------------------------------------------------------------------------------------------
+def moe_route(h: torch.Tensor, w_router: torch.Tensor, top_k: int) -> Tuple[torch.Tensor, torch.Tensor]:
+    """-> expert ids [T, top_k] (int64, most probable first) and their weights [T, top_k]."""
+    logits = linear(h, w_router)
+    prob = torch.exp(logits - logits.max(dim=-1, keepdim=True).values)
+    prob = prob / prob.sum(dim=-1, keepdim=True)
+    n_tokens, n_experts = prob.shape
+    ids = torch.empty((n_tokens, top_k), dtype=torch.int64)
+    wts = torch.empty((n_tokens, top_k), dtype=F64)
+    for t in range(n_tokens):
+        order = sorted(range(n_experts), key=lambda e: (-float(prob[t, e]), e))[:top_k]
+        chosen = prob[t, order]
+        ids[t] = torch.tensor(order)
+        wts[t] = chosen / chosen.sum()
+    return ids, wts
+
+
+def moe_mlp(h: torch.Tensor, w_router: torch.Tensor, w_gate_up: torch.Tensor, w_down: torch.Tensor,
+            top_k: int, routing: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> torch.Tensor:
+    """sum_j weight_j * down_e(j)( silu_mul( gate_up_e(j)( h ) ) ) per token.  `routing` replaces the
+    router's own (ids, weights) when given (teacher-forced checks of an implementation whose
+    near-tie decisions may legitimately differ)."""
+    h = _f64(h)
+    ids, wts = routing if routing is not None else moe_route(h, w_router, top_k)
+    out = torch.zeros_like(h)
+    for e in range(w_gate_up.shape[0]):
+        rows, slots = torch.nonzero(ids == e, as_tuple=True)
+        if rows.numel() == 0:
+            continue
+        y = linear(silu_mul(linear(h[rows], w_gate_up[e])), w_down[e])
+        out.index_add_(0, rows, y * _f64(wts)[rows, slots].unsqueeze(-1))
+    return out
+
+
+# --------------------------------------------------------------------------------------------
 # One layer / whole stack
 # --------------------------------------------------------------------------------------------
 
@@ -241,8 +288,11 @@ def layer_forward(shape: Shape, w: LayerWeights, x: torch.Tensor, cu_seqlens: Se
         v_next.append(v_full)
     x = x + linear(attn_out, w.w_o)
     h2 = rmsnorm(x, w.mlp_norm, shape.rms_eps)
-    act = silu_mul(linear(h2, w.w_gate_up))
-    x = x + linear(act, w.w_down)
+    if w.w_router is not None:
+        x = x + moe_mlp(h2, w.w_router, w.w_gate_up, w.w_down, shape.top_k)
+    else:
+        act = silu_mul(linear(h2, w.w_gate_up))
+        x = x + linear(act, w.w_down)
     return x, k_next, v_next
 
 

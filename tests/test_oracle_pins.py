@@ -362,3 +362,65 @@ def test_sampled_rows_equal_full_layer():
     assert torch.allclose(out, full[rows], rtol=0, atol=1e-13)
     assert torch.allclose(k_rot, torch.cat(k_l), rtol=0, atol=1e-13)
     assert torch.allclose(v_raw, torch.cat(v_l), rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------------
+# Mixture-of-experts FFN (Section 7): pins of the oracle's router + experts.
+# ---------------------------------------------------------------------------------------------
+def _moe_inputs(n=9, d=8, f=6, e=4, seed=70):
+    g = torch.Generator().manual_seed(seed)
+    h = torch.randn((n, d), generator=g, dtype=torch.float64)
+    wr = torch.randn((e, d), generator=g, dtype=torch.float64)
+    wgu = torch.randn((e, 2 * f, d), generator=g, dtype=torch.float64) * 0.5
+    wd = torch.randn((e, d, f), generator=g, dtype=torch.float64) * 0.5
+    return h, wr, wgu, wd
+
+
+def test_moe_identical_experts_equal_the_dense_ffn():
+    h, wr, wgu, wd = _moe_inputs()
+    wgu[:] = wgu[0]
+    wd[:] = wd[0]
+    dense = O.linear(O.silu_mul(O.linear(h, wgu[0])), wd[0])
+    for k in (1, 2, 4):
+        assert torch.allclose(O.moe_mlp(h, wr, wgu, wd, k), dense, rtol=1e-12, atol=1e-12)
+
+
+def test_moe_top_k_equal_to_all_experts_is_the_softmax_weighted_sum():
+    h, wr, wgu, wd = _moe_inputs()
+    prob = torch.softmax(h @ wr.T, dim=-1)
+    want = sum(prob[:, e:e + 1] * O.linear(O.silu_mul(O.linear(h, wgu[e])), wd[e]) for e in range(4))
+    assert torch.allclose(O.moe_mlp(h, wr, wgu, wd, 4), want, rtol=1e-12, atol=1e-12)
+
+
+def test_moe_one_hot_router_selects_that_expert_alone():
+    h, wr, wgu, wd = _moe_inputs()
+    h = h.abs() + 0.1                               # positive features so one row of W_r dominates
+    wr = torch.zeros_like(wr)
+    wr[2] = 50.0
+    want = O.linear(O.silu_mul(O.linear(h, wgu[2])), wd[2])
+    assert torch.allclose(O.moe_mlp(h, wr, wgu, wd, 1), want, rtol=1e-12, atol=1e-12)
+    ids, wts = O.moe_route(h, wr, 1)
+    assert (ids == 2).all() and torch.allclose(wts, torch.ones_like(wts))
+
+
+def test_moe_matches_python_loops_on_tiny_inputs():
+    h, wr, wgu, wd = _moe_inputs(n=5, d=4, f=3, e=4, seed=71)
+    k = 2
+    got = O.moe_mlp(h, wr, wgu, wd, k)
+    ids, wts = O.moe_route(h, wr, k)
+    for t in range(h.shape[0]):
+        logits = [sum(float(h[t, c]) * float(wr[e, c]) for c in range(4)) for e in range(4)]
+        mx = max(logits)
+        ex = [math.exp(v - mx) for v in logits]
+        prob = [v / sum(ex) for v in ex]
+        order = sorted(range(4), key=lambda e: (-prob[e], e))[:k]
+        assert [int(i) for i in ids[t]] == order
+        norm = sum(prob[e] for e in order)
+        want = [0.0] * 4
+        for e in order:
+            gu = [sum(float(h[t, c]) * float(wgu[e, r, c]) for c in range(4)) for r in range(6)]
+            act = [gu[r] / (1.0 + math.exp(-gu[r])) * gu[3 + r] for r in range(3)]
+            y = [sum(act[r] * float(wd[e, c, r]) for r in range(3)) for c in range(4)]
+            want = [want[c] + prob[e] / norm * y[c] for c in range(4)]
+        assert torch.allclose(got[t], torch.tensor(want, dtype=torch.float64), rtol=1e-10, atol=1e-12)
+        assert abs(float(wts[t].sum()) - 1.0) < 1e-12 and len(set(order)) == k
