@@ -34,6 +34,14 @@
  *   0 rmsnorm_attn  1 qkv_proj  2 rope_kvwrite  3 attn  4 o_proj(+residual)
  *   5 rmsnorm_mlp   6 gate_up_proj  7 silu_mul  8 down_proj(+residual)
  * The paper's five boundaries are after positions 1, 3, 4, 6, 8.
+ *
+ * Mixture-of-experts models (Section 7: the FFN becomes the two operators `gate` and `experts`)
+ * keep the nine positions; 6-8 become
+ *   6 gate          router logits, softmax over all experts, top_k experts per token (ties: lower
+ *                   index), probabilities renormalised over the selected experts
+ *   7 experts_up    tokens gathered per expert; gate/up projection + SiLU*up of every expert
+ *   8 experts_down  down projection of every expert; weighted sum into the residual stream
+ * so the paper's boundaries (after gate, after experts) are again positions 6 and 8.
  */
 #ifndef FLOWPREFILL_H
 #define FLOWPREFILL_H
@@ -73,6 +81,8 @@ typedef struct {
   int32_t kv_block_tokens;  /* tokens per KV block; must be 16                                   */
   int64_t kv_num_blocks;    /* size of the block pool; one block id addresses all layers         */
   int32_t max_position;     /* RoPE table length = largest sequence length (prefix + new tokens) */
+  int32_t n_experts;        /* 0 = dense FFN.  > 0: mixture-of-experts FFN (Section 7), bf16 only: */
+  int32_t top_k;            /*   top_k of n_experts experts per token, `ffn` = one expert's width  */
 } fp_shape;
 
 /* Device pointers, BORROWED: the caller owns them and keeps them alive and unchanged for the
@@ -81,6 +91,9 @@ typedef struct {
  * All must be 16-byte aligned.                                                                   */
 typedef struct {
   const void *attn_norm, *w_qkv, *w_o, *mlp_norm, *w_gate_up, *w_down;
+  const void* w_router;     /* mixture-of-experts models only (else NULL): [n_experts, hidden];
+                             * then w_gate_up is [n_experts, 2*ffn, hidden] and w_down
+                             * [n_experts, hidden, ffn], one expert after the other            */
 } fp_layer_weights;
 
 /* Creates a model: validates the shape (hidden, Hq*D, ffn multiples of 8; head_dim 64 or 128 on
@@ -181,6 +194,14 @@ fp_status fp_prefill_kv_gather(const fp_prefill* task, int32_t layer, int32_t se
 fp_status fp_prefill_set_timing(fp_prefill* task, int32_t on);
 fp_status fp_prefill_op_times(fp_prefill* task, float* ms_out /*host*/, int32_t n,
                               int32_t* n_out /*host*/);
+
+/* Mixture-of-experts models: copies layer `layer`'s routing decision -- expert ids [T, top_k]
+ * (int32, most probable first) and renormalised weights [T, top_k] (fp32) -- to device buffers.
+ * Valid once the cursor has passed that layer's gate operator (FP_ERR_STATE before); waits for
+ * the stream.  Tests use it to hand the same decision to a reference when two experts are a
+ * rounding error apart.                                                                          */
+fp_status fp_prefill_moe_routing(fp_prefill* task, int32_t layer, int32_t* ids_out /*device*/,
+                                 float* weights_out /*device*/);
 
 /* Ends a task in any state except while an advance is running: returns its workspace to the
  * model's cache and frees the KV blocks the library allocated for it.  "Running" lasts until

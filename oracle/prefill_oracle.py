@@ -217,13 +217,38 @@ def moe_route(h: torch.Tensor, w_router: torch.Tensor, top_k: int) -> Tuple[torc
     return ids, wts
 
 
+def moe_weights_for(h: torch.Tensor, w_router: torch.Tensor, ids: torch.Tensor) -> torch.Tensor:
+    """The renormalised router probabilities of GIVEN expert ids [T, k] (any order)."""
+    prob = torch.softmax(linear(h, w_router), dim=-1)
+    chosen = torch.gather(prob, 1, ids.to(torch.int64))
+    return chosen / chosen.sum(dim=-1, keepdim=True)
+
+
+def moe_selection_shortfall(h: torch.Tensor, w_router: torch.Tensor, ids: torch.Tensor,
+                            top_k: int) -> torch.Tensor:
+    """Per token: (the oracle's k-th largest router probability) - (the smallest probability among
+    the given experts), clipped at 0.  Zero when `ids` is a top-k set of the oracle's
+    probabilities; a value of the order of the implementation's rounding error means the
+    implementation resolved a near-tie the other way."""
+    prob = torch.softmax(linear(h, w_router), dim=-1)
+    kth = torch.sort(prob, dim=-1, descending=True).values[:, top_k - 1]
+    weakest = torch.gather(prob, 1, ids.to(torch.int64).cpu()).min(dim=-1).values
+    return torch.clamp(kth - weakest, min=0.0)
+
+
 def moe_mlp(h: torch.Tensor, w_router: torch.Tensor, w_gate_up: torch.Tensor, w_down: torch.Tensor,
-            top_k: int, routing: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> torch.Tensor:
-    """sum_j weight_j * down_e(j)( silu_mul( gate_up_e(j)( h ) ) ) per token.  `routing` replaces the
-    router's own (ids, weights) when given (teacher-forced checks of an implementation whose
-    near-tie decisions may legitimately differ)."""
+            top_k: int, forced_ids: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """sum_j weight_j * down_e(j)( silu_mul( gate_up_e(j)( h ) ) ) per token.  `forced_ids` [T, k]
+    replaces the router's own SELECTION (the weights stay the oracle's own probabilities of those
+    experts, renormalised): for checking an implementation whose decision between two experts a
+    rounding error apart may legitimately differ -- the test then also checks that the forced
+    selection is a valid top-k of the oracle's probabilities to within that rounding error."""
     h = _f64(h)
-    ids, wts = routing if routing is not None else moe_route(h, w_router, top_k)
+    if forced_ids is not None:
+        ids = forced_ids.to(torch.int64).cpu()
+        wts = moe_weights_for(h, w_router, ids)
+    else:
+        ids, wts = moe_route(h, w_router, top_k)
     out = torch.zeros_like(h)
     for e in range(w_gate_up.shape[0]):
         rows, slots = torch.nonzero(ids == e, as_tuple=True)
@@ -256,7 +281,9 @@ class KVState:
 
 
 def layer_forward(shape: Shape, w: LayerWeights, x: torch.Tensor, cu_seqlens: Sequence[int],
-                  k_prev: List[torch.Tensor], v_prev: List[torch.Tensor]
+                  k_prev: List[torch.Tensor], v_prev: List[torch.Tensor],
+                  forced_ids: Optional[torch.Tensor] = None,
+                  shortfall_out: Optional[List[torch.Tensor]] = None
                   ) -> Tuple[torch.Tensor, List[torch.Tensor], List[torch.Tensor]]:
     """One decoder layer over a packed batch.
 
@@ -289,7 +316,9 @@ def layer_forward(shape: Shape, w: LayerWeights, x: torch.Tensor, cu_seqlens: Se
     x = x + linear(attn_out, w.w_o)
     h2 = rmsnorm(x, w.mlp_norm, shape.rms_eps)
     if w.w_router is not None:
-        x = x + moe_mlp(h2, w.w_router, w.w_gate_up, w.w_down, shape.top_k)
+        if forced_ids is not None and shortfall_out is not None:
+            shortfall_out.append(moe_selection_shortfall(h2, w.w_router, forced_ids, shape.top_k))
+        x = x + moe_mlp(h2, w.w_router, w.w_gate_up, w.w_down, shape.top_k, forced_ids)
     else:
         act = silu_mul(linear(h2, w.w_gate_up))
         x = x + linear(act, w.w_down)
@@ -297,8 +326,9 @@ def layer_forward(shape: Shape, w: LayerWeights, x: torch.Tensor, cu_seqlens: Se
 
 
 def prefill(shape: Shape, layers: Sequence[LayerWeights], x: torch.Tensor,
-            cu_seqlens: Sequence[int], cache: Optional[KVState] = None
-            ) -> Tuple[torch.Tensor, KVState]:
+            cu_seqlens: Sequence[int], cache: Optional[KVState] = None,
+            forced_ids: Optional[Sequence[torch.Tensor]] = None,
+            shortfall_out: Optional[List[torch.Tensor]] = None) -> Tuple[torch.Tensor, KVState]:
     """The whole stack over a packed batch of (chunks of) prompts.  `cache` carries what earlier
     chunks of the same sequences left behind (None = empty).  Returns the final residual stream
     [T, d] and the extended cache."""
@@ -309,7 +339,8 @@ def prefill(shape: Shape, layers: Sequence[LayerWeights], x: torch.Tensor,
     new_k, new_v = [], []
     for layer in range(shape.n_layers):
         x, k_l, v_l = layer_forward(shape, layers[layer], x, cu_seqlens,
-                                    cache.k[layer], cache.v[layer])
+                                    cache.k[layer], cache.v[layer],
+                                    None if forced_ids is None else forced_ids[layer], shortfall_out)
         new_k.append(k_l)
         new_v.append(v_l)
     return x, KVState(k=new_k, v=new_v)

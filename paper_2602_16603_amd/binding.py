@@ -28,6 +28,7 @@ FP_OPS_PER_LAYER = 9
 FP_BOUNDARY_EVERY_OP, FP_BOUNDARY_PAPER_OPS, FP_BOUNDARY_LAYER, FP_BOUNDARY_NONE = 0x1FF, 0x15A, 0x100, 0x0
 OP_NAMES = ("rmsnorm_attn", "qkv_proj", "rope_kvwrite", "attn", "o_proj", "rmsnorm_mlp",
             "gate_up_proj", "silu_mul", "down_proj")
+MOE_OP_NAMES = OP_NAMES[:6] + ("gate", "experts_up", "experts_down")
 
 
 class fp_shape(C.Structure):
@@ -35,12 +36,13 @@ class fp_shape(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32),
                 ("kv_block_tokens", C.c_int32), ("kv_num_blocks", C.c_int64),
-                ("max_position", C.c_int32)]
+                ("max_position", C.c_int32), ("n_experts", C.c_int32), ("top_k", C.c_int32)]
 
 
 class fp_layer_weights(C.Structure):
     _fields_ = [("attn_norm", C.c_void_p), ("w_qkv", C.c_void_p), ("w_o", C.c_void_p),
-                ("mlp_norm", C.c_void_p), ("w_gate_up", C.c_void_p), ("w_down", C.c_void_p)]
+                ("mlp_norm", C.c_void_p), ("w_gate_up", C.c_void_p), ("w_down", C.c_void_p),
+                ("w_router", C.c_void_p)]
 
 
 _P = C.c_void_p
@@ -64,6 +66,7 @@ _SIGS = {
     "fp_prefill_kv_gather": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P]),
     "fp_prefill_set_timing": (C.c_int, [_P, C.c_int32]),
     "fp_prefill_op_times": (C.c_int, [_P, C.POINTER(C.c_float), C.c_int32, _I32P]),
+    "fp_prefill_moe_routing": (C.c_int, [_P, C.c_int32, _P, _P]),
     "fp_prefill_end": (None, [_P]),
     "fp_op_gemm": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _P]),
     "fp_op_rmsnorm": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_float, _P]),
@@ -123,7 +126,7 @@ def fp_model_create(shape: fp_shape, layers: Sequence[Dict[str, int]], hip_strea
     arr = (fp_layer_weights * len(layers))()
     for i, w in enumerate(layers):
         for name, _ in fp_layer_weights._fields_:
-            setattr(arr[i], name, int(w[name]))
+            setattr(arr[i], name, int(w.get(name, 0)))          # w_router: mixture-of-experts models only
     out = _P()
     _check(lib.fp_model_create(C.byref(shape), arr, _P(hip_stream), C.byref(out)), "fp_model_create")
     return out.value
@@ -247,6 +250,10 @@ def fp_op_rmsnorm(dtype: int, x_f32: int, gain: int, out: int, t: int, d: int, e
            "fp_op_rmsnorm")
 
 
+def fp_prefill_moe_routing(task: int, layer: int, ids_out: int, weights_out: int) -> None:
+    _check(lib.fp_prefill_moe_routing(_P(task), layer, _P(ids_out), _P(weights_out)), "fp_prefill_moe_routing")
+
+
 def fp_op_silu_mul(dtype: int, gu: int, out: int, t: int, f: int, hip_stream: int = 0) -> None:
     _check(lib.fp_op_silu_mul(dtype, _P(gu), _P(out), t, f, _P(hip_stream)), "fp_op_silu_mul")
 
@@ -258,7 +265,8 @@ def fp_op_gemm_swiglu(a: int, w_gate_up: int, out: int, m: int, f: int, k: int, 
 def make_shape(spec, dtype: int, kv_num_blocks: int, max_position: int) -> fp_shape:
     """fp_shape from an inputs.ShapeSpec-like object (plain attribute copy)."""
     return fp_shape(spec.n_layers, spec.hidden, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
-                    spec.ffn, spec.rms_eps, spec.rope_theta, dtype, 16, kv_num_blocks, max_position)
+                    spec.ffn, spec.rms_eps, spec.rope_theta, dtype, 16, kv_num_blocks, max_position,
+                    getattr(spec, "n_experts", 0), getattr(spec, "top_k", 0))
 
 
 # ---- event-driven scheduler (host-only) ----

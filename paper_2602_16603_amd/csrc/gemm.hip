@@ -278,12 +278,19 @@ __device__ __forceinline__ void pp_barrier() {
 // gate_up GEMM + silu_mul operators produce, without the [M][2N] round trip through HBM.
 enum { kEpiBf16 = 0, kEpiResidual = 1, kEpiPartial = 2, kEpiSwiGLU = 3 };
 
-template <int EPI>
+//
+// GROUPED (mixture-of-experts): the launch covers many independent problems that share N and K.
+// groups[0] = number of row tiles; entry i (three ints from groups[1 + 3 i]) = {expert, first
+// row, rows (<= 256)}: the tile multiplies rows [first, first + rows) of A with expert's weight
+// matrix (W holds the experts' matrices back to back) into the same rows of C.  The grid is sized
+// for the worst case on the host; workgroups past groups[0] row tiles return at once.
+template <int EPI, bool GROUPED = false>
 __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restrict__ A,
                                                            const bf16* __restrict__ W,
                                                            void* __restrict__ Cout, int M, int N,
                                                            int K, int tiles_m, int tiles_n,
-                                                           int kt_per_split) {
+                                                           int kt_per_split,
+                                                           const int32_t* __restrict__ groups) {
   constexpr bool RESID = EPI == kEpiResidual;
   constexpr bool SWIGLU = EPI == kEpiSwiGLU;
   constexpr int BM = 256, BN = SWIGLU ? 128 : 256;   // output columns per tile
@@ -299,8 +306,20 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
   const int wm = wave & 1, wn = wave >> 1;           // 2 x 4 waves, wave tile 128 x 64
   int tile_m, tile_n;
   const int n_tiles = tiles_m * tiles_n;
-  const int split = blockIdx.x / n_tiles;            // which K range (0 unless split-K)
-  tile_of_workgroup(blockIdx.x - split * n_tiles, tiles_m, tiles_n, tile_m, tile_n);
+  const int split = GROUPED ? 0 : blockIdx.x / n_tiles;   // which K range (0 unless split-K)
+  if (GROUPED) {
+    const int ti = blockIdx.x / tiles_n;
+    if (ti >= groups[0]) return;                     // whole workgroup, before any barrier
+    const int expert = groups[1 + 3 * ti], first = groups[2 + 3 * ti];
+    M = groups[3 + 3 * ti];
+    A += (int64_t)first * K;
+    W += (int64_t)expert * (EPI == kEpiSwiGLU ? 2 : 1) * N * K;
+    Cout = reinterpret_cast<char*>(Cout) + (int64_t)first * N * (EPI == kEpiBf16 || EPI == kEpiSwiGLU ? 2 : 4);
+    tile_m = 0;
+    tile_n = blockIdx.x - ti * tiles_n;
+  } else {
+    tile_of_workgroup(blockIdx.x - split * n_tiles, tiles_m, tiles_n, tile_m, tile_n);
+  }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int kt_first = split * kt_per_split;
   const int kt_count = min(kt_per_split, K / kBK - kt_first);
@@ -523,7 +542,19 @@ void launch_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t
   const int tiles_m = (int)((m + 255) / 256), tiles_n = (int)((f + 127) / 128);
   gemm_bf16_pp_kernel<kEpiSwiGLU><<<dim3((unsigned)(tiles_m * tiles_n)), 512, 0, s>>>(
       (const bf16*)a, (const bf16*)w_gate_up, out, (int)m, (int)f, (int)k, tiles_m, tiles_n,
-      (int)(k / kBK));
+      (int)(k / kBK), nullptr);
+}
+
+void launch_gemm_grouped(const void* a, const void* w, void* c, int64_t n, int64_t k, int swiglu,
+                         const int32_t* groups, int max_row_tiles, hipStream_t s) {
+  const int tiles_n = (int)(swiglu ? (n + 127) / 128 : (n + 255) / 256);
+  const dim3 grid((unsigned)(max_row_tiles * tiles_n));
+  if (swiglu)
+    gemm_bf16_pp_kernel<kEpiSwiGLU, true><<<grid, 512, 0, s>>>((const bf16*)a, (const bf16*)w, c, 0, (int)n,
+                                                              (int)k, max_row_tiles, tiles_n, (int)(k / kBK), groups);
+  else
+    gemm_bf16_pp_kernel<kEpiBf16, true><<<grid, 512, 0, s>>>((const bf16*)a, (const bf16*)w, c, 0, (int)n,
+                                                            (int)k, max_row_tiles, tiles_n, (int)(k / kBK), groups);
 }
 
 size_t gemm_workspace_bytes(int dtype, int64_t m, int64_t n, int64_t k) {
@@ -539,13 +570,13 @@ static void launch_bf16_pp(const bf16* a, const bf16* w, void* c, int m, int n, 
   const int kt = k / kBK;
   if (splits <= 1) {
     gemm_bf16_pp_kernel<RESID ? kEpiResidual : kEpiBf16>
-        <<<dim3((unsigned)(tiles_m * tiles_n)), 512, 0, s>>>(a, w, c, m, n, k, tiles_m, tiles_n, kt);
+        <<<dim3((unsigned)(tiles_m * tiles_n)), 512, 0, s>>>(a, w, c, m, n, k, tiles_m, tiles_n, kt, nullptr);
     return;
   }
   const int per = (kt + splits - 1) / splits;
   const int used = (kt + per - 1) / per;             // every launched split has at least one k-tile
   gemm_bf16_pp_kernel<kEpiPartial><<<dim3((unsigned)(tiles_m * tiles_n * used)), 512, 0, s>>>(
-      a, w, workspace, m, n, k, tiles_m, tiles_n, per);
+      a, w, workspace, m, n, k, tiles_m, tiles_n, per, nullptr);
   const int64_t mn = (int64_t)m * n;
   splitk_reduce_kernel<RESID><<<dim3((unsigned)((mn / 8 + 255) / 256)), 256, 0, s>>>(workspace, c, mn / 8,
                                                                                    mn, used);

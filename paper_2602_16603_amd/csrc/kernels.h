@@ -57,12 +57,30 @@ size_t gemm_workspace_bytes(int dtype, int64_t m, int64_t n, int64_t k);
 bool gemm_swiglu_fusable(int dtype, int64_t m, int64_t f, int64_t k);
 void launch_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t m, int64_t f,
                         int64_t k, hipStream_t s);
+// Grouped bf16 GEMM for mixture-of-experts layers (K % 64 == 0, n % 8 == 0): `groups` (device) =
+// {row tiles, then {expert, first row, rows <= 256} per row tile}; row tile i multiplies those
+// rows of a [*, k] with expert's matrix of w ([experts][n][k], or [experts][2n][k] gate rows then
+// up rows when swiglu) into the same rows of c [*, n] (bf16; swiglu: silu(gate)*up).  The grid
+// covers max_row_tiles row tiles; the surplus exits.
+void launch_gemm_grouped(const void* a, const void* w, void* c, int64_t n, int64_t k, int swiglu,
+                         const int32_t* groups, int max_row_tiles, hipStream_t s);
 
 // Gathers positions 0..len-1 of one sequence (block table row `table_dev`, device) of one layer
 // into contiguous k_out/v_out [len, Hkv, D].
 void launch_kv_gather(int dtype, const void* k_pool, const void* v_pool, void* k_out, void* v_out,
                       int len, const Geometry& g, int layer, const int32_t* table_dev,
                       hipStream_t s);
+
+// Mixture-of-experts FFN (bf16 path).  plan = device int32 [3 * n_experts]: counts | row offsets |
+// cursors; groups = device int32 [1 + 3 * (n_tokens*top_k/256 + n_experts)]: the row-tile table
+// launch_gemm_grouped reads.  counts must be zero before launch_moe_route.
+void launch_fill_zero(void* p, int64_t n_dwords, hipStream_t s);
+void launch_moe_route(const float* logits, int32_t* ids, float* wts, int32_t* plan, int32_t* groups,
+                      int64_t n_tokens, int n_experts, int top_k, hipStream_t s);
+void launch_moe_gather(const void* h, void* hp, const int32_t* ids, int32_t* plan, int32_t* slot_of,
+                       int64_t n_tokens, int top_k, int n_experts, int d, hipStream_t s);
+void launch_moe_combine(float* x, const void* y, const int32_t* slot_of, const float* wts,
+                        int64_t n_tokens, int top_k, int d, hipStream_t s);
 
 // Sets the calling thread's fp_last_error() text (for translation units other than the runtime).
 void set_last_error(const char* message);

@@ -1,0 +1,170 @@
+// Mixture-of-experts FFN support (FlowPrefill Section 7, "Mixture-of-Experts (MoE) models": the
+// `gate` operator -- a gated router -- and the `experts` operator -- several expert FFNs).
+// Router: softmax over all experts of h W_r^T, the top_k most probable experts per token (ties:
+// lower index), probabilities renormalised over the selected ones.  The expert FFNs run as two
+// grouped GEMMs over the tokens gathered per expert (the second one's rows are then combined,
+// weighted, into the residual stream).  The arithmetic of a token never depends on where in an
+// expert's row range it lands, so the (atomic, run-to-run varying) slot order does not reach the
+// results.
+#include "common.h"
+#include "kernels.h"
+
+namespace fp {
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+void launch_fill_zero(void* p, int64_t n_dwords, hipStream_t s) {
+  if (n_dwords <= 0) return;
+  fill_zero_kernel<<<dim3((unsigned)((n_dwords + 255) / 256)), 256, 0, s>>>((uint32_t*)p, n_dwords);
+}
+
+// One wave per token: probabilities, top_k selection, renormalised weights, per-expert counts.
+// n_experts <= 256 (lane l holds experts l, l+64, l+128, l+192), top_k <= 8.
+__global__ __launch_bounds__(256) void moe_route_kernel(const float* __restrict__ logits,
+                                                        int32_t* __restrict__ ids,
+                                                        float* __restrict__ wts,
+                                                        int32_t* __restrict__ counts, int n_tokens,
+                                                        int n_experts, int top_k) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= n_tokens) return;
+  float p[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int e = lane + 64 * i;
+    p[i] = e < n_experts ? logits[(int64_t)t * n_experts + e] : -INFINITY;
+  }
+  float mx = fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3]));
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    p[i] = lane + 64 * i < n_experts ? expf(p[i] - mx) : -1.0f;   // -1: never selected
+    sum += fmaxf(p[i], 0.f);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) p[i] = p[i] >= 0.f ? p[i] * inv : -1.0f;
+
+  float chosen_p[8];
+  int chosen_e[8];
+  float total = 0.f;
+  for (int j = 0; j < top_k; ++j) {
+    float bv = p[0];
+    int be = lane;
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+      if (p[i] > bv) { bv = p[i]; be = lane + 64 * i; }          // own experts ascend with i: ties keep the lower
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(bv, o);
+      const int oe = __shfl_xor(be, o);
+      if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+    }
+    chosen_p[j] = bv;
+    chosen_e[j] = be;
+    total += bv;
+    if ((be & 63) == lane) p[be >> 6] = -1.0f;                    // taken
+  }
+  if (lane == 0) {
+    const float norm = 1.0f / total;
+    for (int j = 0; j < top_k; ++j) {
+      ids[(int64_t)t * top_k + j] = chosen_e[j];
+      wts[(int64_t)t * top_k + j] = chosen_p[j] * norm;
+      atomicAdd(&counts[chosen_e[j]], 1);
+    }
+  }
+}
+
+// One thread: per-expert row offsets, the grouped GEMMs' row-tile table, cursors reset.
+//   plan[0 .. E)      counts (input)     plan[E .. 2E)  offsets     plan[2E .. 3E)  cursors
+//   groups[0] = row tiles, then {expert, first row, rows} per tile (256-row tiles)
+__global__ void moe_plan_kernel(int32_t* __restrict__ plan, int32_t* __restrict__ groups, int n_experts) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  int offset = 0, n = 0;
+  for (int e = 0; e < n_experts; ++e) {
+    const int c = plan[e];
+    plan[n_experts + e] = offset;
+    plan[2 * n_experts + e] = 0;
+    for (int m = 0; m < c; m += 256) {
+      groups[1 + 3 * n] = e;
+      groups[2 + 3 * n] = offset + m;
+      groups[3 + 3 * n] = min(256, c - m);
+      ++n;
+    }
+    offset += c;
+  }
+  groups[0] = n;
+}
+
+// One wave per (token, choice): take the next free row of the expert's range and copy the
+// token's activations there.
+__global__ __launch_bounds__(256) void moe_gather_kernel(const bf16* __restrict__ h,
+                                                         bf16* __restrict__ hp,
+                                                         const int32_t* __restrict__ ids,
+                                                         int32_t* __restrict__ plan,
+                                                         int32_t* __restrict__ slot_of, int n_pairs,
+                                                         int top_k, int n_experts, int d) {
+  const int lane = threadIdx.x & 63;
+  const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (pair >= n_pairs) return;
+  int slot = 0;
+  if (lane == 0) {
+    const int e = ids[pair];
+    slot = plan[n_experts + e] + atomicAdd(&plan[2 * n_experts + e], 1);
+    slot_of[pair] = slot;
+  }
+  slot = __shfl(slot, 0);
+  const u32x4* src = reinterpret_cast<const u32x4*>(h + (int64_t)(pair / top_k) * d);
+  u32x4* dst = reinterpret_cast<u32x4*>(hp + (int64_t)slot * d);
+  for (int c = lane; c < d / 8; c += 64) dst[c] = src[c];
+}
+
+// x[t] += sum_j wts[t][j] * y[slot_of[t][j]], j ascending, fp32.
+__global__ __launch_bounds__(256) void moe_combine_kernel(float* __restrict__ x,
+                                                          const bf16* __restrict__ y,
+                                                          const int32_t* __restrict__ slot_of,
+                                                          const float* __restrict__ wts, int64_t n_tokens,
+                                                          int top_k, int d) {
+  const int64_t d8 = d / 8;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_tokens * d8) return;
+  const int64_t t = i / d8, c = i - t * d8;
+  f32x8 acc = Vec8<float>::load(x + t * d + c * 8);
+  for (int j = 0; j < top_k; ++j) {
+    const float w = wts[t * top_k + j];
+    const f32x8 v = Vec8<bf16>::load(y + (int64_t)slot_of[t * top_k + j] * d + c * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = fmaf(w, v[e], acc[e]);
+  }
+  Vec8<float>::store(x + t * d + c * 8, acc);
+}
+
+void launch_moe_route(const float* logits, int32_t* ids, float* wts, int32_t* plan, int32_t* groups,
+                      int64_t n_tokens, int n_experts, int top_k, hipStream_t s) {
+  moe_route_kernel<<<dim3((unsigned)((n_tokens + 3) / 4)), 256, 0, s>>>(logits, ids, wts, plan, (int)n_tokens,
+                                                                        n_experts, top_k);
+  moe_plan_kernel<<<1, 64, 0, s>>>(plan, groups, n_experts);
+}
+
+void launch_moe_gather(const void* h, void* hp, const int32_t* ids, int32_t* plan, int32_t* slot_of,
+                       int64_t n_tokens, int top_k, int n_experts, int d, hipStream_t s) {
+  const int64_t pairs = n_tokens * top_k;
+  moe_gather_kernel<<<dim3((unsigned)((pairs + 3) / 4)), 256, 0, s>>>((const bf16*)h, (bf16*)hp, ids, plan, slot_of,
+                                                                      (int)pairs, top_k, n_experts, d);
+}
+
+void launch_moe_combine(float* x, const void* y, const int32_t* slot_of, const float* wts,
+                        int64_t n_tokens, int top_k, int d, hipStream_t s) {
+  const int64_t n = n_tokens * (d / 8);
+  moe_combine_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, s>>>(x, (const bf16*)y, slot_of, wts, n_tokens,
+                                                                       top_k, d);
+}
+
+}  // namespace fp

@@ -94,6 +94,11 @@ struct fp_prefill {
   // carved out of ws:
   float* x = nullptr;
   void *h = nullptr, *qkv = nullptr, *o = nullptr, *gu = nullptr, *act = nullptr;
+  // mixture-of-experts scratch (device; null for dense models)
+  float* moe_logits = nullptr; float* moe_wts = nullptr;
+  int32_t *moe_ids = nullptr, *moe_slot = nullptr, *moe_plan = nullptr, *moe_groups = nullptr;
+  void *moe_hp = nullptr, *moe_act = nullptr, *moe_y = nullptr;
+  int32_t moe_max_row_tiles = 0;
   bool swiglu_fused = false;   // op 6 writes act directly (fused epilogue); op 7 then has no work and gu is not allocated
   void* splitk = nullptr;              // split-K partial sums (0 bytes when no GEMM of this task splits)
   size_t splitk_bytes = 0;
@@ -123,6 +128,31 @@ fp_status launch_op(fp_prefill* t, int32_t index) {
   const int64_t T = t->n_tokens, d = sh.hidden, F = sh.ffn;
   const int64_t qd = (int64_t)sh.n_q_heads * sh.head_dim;
   hipStream_t s = m->stream;
+  if (sh.n_experts > 0 && op >= 6) {
+    const int E = sh.n_experts, k = sh.top_k;
+    int32_t* ids = t->moe_ids + (int64_t)layer * T * k;      // kept per layer for inspection
+    float* wts = t->moe_wts + (int64_t)layer * T * k;
+    switch (op) {
+      case 6:   // gate: router logits (fp32, accumulated into zeros), selection, row plan
+        fp::launch_fill_zero(t->moe_logits, T * E, s);
+        fp::launch_fill_zero(t->moe_plan, E, s);
+        fp::launch_gemm(dt, t->h, w.w_router, t->moe_logits, T, E, d, 1, t->splitk, t->splitk_bytes, s);
+        fp::launch_moe_route(t->moe_logits, ids, wts, t->moe_plan, t->moe_groups, T, E, k, s);
+        break;
+      case 7:   // experts, first half: gather per expert, gate/up projection + SiLU*up
+        fp::launch_moe_gather(t->h, t->moe_hp, ids, t->moe_plan, t->moe_slot, T, k, E, (int)d, s);
+        fp::launch_gemm_grouped(t->moe_hp, w.w_gate_up, t->moe_act, F, d, 1, t->moe_groups, t->moe_max_row_tiles, s);
+        break;
+      case 8:   // experts, second half: down projection, weighted sum into the residual stream
+        fp::launch_gemm_grouped(t->moe_act, w.w_down, t->moe_y, d, F, 0, t->moe_groups, t->moe_max_row_tiles, s);
+        fp::launch_moe_combine(t->x, t->moe_y, t->moe_slot, wts, T, k, (int)d, s);
+        break;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+      return fail(FP_ERR_DEVICE, "launch of layer %d op %d failed: %s", layer, op, hipGetErrorString(e));
+    return FP_OK;
+  }
   switch (op) {
     case 0: fp::launch_rmsnorm(dt, t->x, w.attn_norm, t->h, T, d, sh.rms_eps, s); break;
     case 1: fp::launch_gemm(dt, t->h, w.w_qkv, t->qkv, T, m->geo.qkv_width(), d, 0, t->splitk, t->splitk_bytes, s); break;
@@ -203,11 +233,20 @@ fp_status fp_model_create(const fp_shape* shape, const fp_layer_weights* layers,
       s.head_dim != 128)
     return fail(FP_ERR_INVALID, "fp32 path supports head_dim 16, 32, 64 or 128");
   if (s.kv_num_blocks > INT32_MAX) return fail(FP_ERR_INVALID, "kv_num_blocks too large");
+  if (s.n_experts < 0 || s.top_k < 0 || (s.n_experts == 0) != (s.top_k == 0))
+    return fail(FP_ERR_INVALID, "n_experts and top_k must both be zero (dense) or both positive");
+  if (s.n_experts > 0) {
+    if (s.dtype != FP_DTYPE_BF16) return fail(FP_ERR_INVALID, "mixture-of-experts models are bf16 only");
+    if (s.n_experts > 256 || s.n_experts % 8 || s.top_k > 8 || s.top_k > s.n_experts)
+      return fail(FP_ERR_INVALID, "n_experts must be a multiple of 8 up to 256, top_k at most 8 and n_experts");
+    if (s.hidden % 64 || s.ffn % 64)
+      return fail(FP_ERR_INVALID, "mixture-of-experts models need hidden and ffn multiples of 64");
+  }
   for (int l = 0; l < s.n_layers; ++l) {
-    const void* ptrs[6] = {layers[l].attn_norm, layers[l].w_qkv, layers[l].w_o,
-                           layers[l].mlp_norm, layers[l].w_gate_up, layers[l].w_down};
-    for (const void* p : ptrs)
-      if (!p || (reinterpret_cast<uintptr_t>(p) & 15))
+    const void* ptrs[7] = {layers[l].attn_norm, layers[l].w_qkv, layers[l].w_o, layers[l].mlp_norm,
+                           layers[l].w_gate_up, layers[l].w_down, layers[l].w_router};
+    for (int i = 0; i < (s.n_experts > 0 ? 7 : 6); ++i)
+      if (!ptrs[i] || (reinterpret_cast<uintptr_t>(ptrs[i]) & 15))
         return fail(FP_ERR_INVALID, "layer %d: null or misaligned weight pointer", l);
   }
   fp_model* m = new (std::nothrow) fp_model();
@@ -406,13 +445,24 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   const size_t Tn = (size_t)std::max(T, 1);
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
-  t->swiglu_fused = fp::gemm_swiglu_fusable(sh.dtype, T, (int64_t)F, (int64_t)d);
+  const bool moe = sh.n_experts > 0;
+  const size_t E = (size_t)sh.n_experts, pairs = Tn * (size_t)sh.top_k;
+  t->swiglu_fused = !moe && fp::gemm_swiglu_fusable(sh.dtype, T, (int64_t)F, (int64_t)d);
   const size_t o_x = carve(Tn * d * 4), o_h = carve(Tn * d * e), o_qkv = carve(Tn * W * e),
-               o_o = carve(Tn * qd * e), o_gu = carve(t->swiglu_fused ? 0 : Tn * 2 * F * e),
-               o_act = carve(Tn * F * e);
+               o_o = carve(Tn * qd * e), o_gu = carve(t->swiglu_fused || moe ? 0 : Tn * 2 * F * e),
+               o_act = carve(moe ? 0 : Tn * F * e);
+  // Mixture-of-experts scratch: every (token, choice) pair owns one row of the gathered buffers.
+  t->moe_max_row_tiles = moe ? (int32_t)(pairs / 256 + E) : 0;
+  const size_t o_ml = carve(moe ? Tn * E * 4 : 0), o_mw = carve(moe ? pairs * 4 * sh.n_layers : 0),
+               o_mi = carve(moe ? pairs * 4 * sh.n_layers : 0), o_ms = carve(moe ? pairs * 4 : 0),
+               o_mp = carve(moe ? 3 * E * 4 : 0), o_mg = carve(moe ? (1 + 3 * (size_t)t->moe_max_row_tiles) * 4 : 0),
+               o_mh = carve(moe ? pairs * d * e : 0), o_ma = carve(moe ? pairs * F * e : 0),
+               o_my = carve(moe ? pairs * d * e : 0);
+  const size_t sk_dense = std::max(fp::gemm_workspace_bytes(sh.dtype, T, 2 * (int64_t)F, (int64_t)d),
+                                   fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)d, (int64_t)F));
   const size_t sk_bytes = std::max(
       std::max(fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)W, (int64_t)d), fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)d, (int64_t)qd)),
-      std::max(fp::gemm_workspace_bytes(sh.dtype, T, 2 * (int64_t)F, (int64_t)d), fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)d, (int64_t)F)));
+      moe ? fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)E, (int64_t)d) : sk_dense);
   const size_t o_sk = carve(sk_bytes);
   const size_t n_int = tok_seq.size() + tok_pos.size() + t->cu.size() + t->cached.size() +
                        t->tables.size() + kv_items.size() + attn_items.size();
@@ -427,6 +477,12 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   t->x = reinterpret_cast<float*>(base + o_x);
   t->splitk = sk_bytes ? base + o_sk : nullptr; t->splitk_bytes = sk_bytes;
   t->h = base + o_h; t->qkv = base + o_qkv; t->o = base + o_o; t->gu = base + o_gu; t->act = base + o_act;
+  if (moe) {
+    t->moe_logits = reinterpret_cast<float*>(base + o_ml); t->moe_wts = reinterpret_cast<float*>(base + o_mw);
+    t->moe_ids = reinterpret_cast<int32_t*>(base + o_mi); t->moe_slot = reinterpret_cast<int32_t*>(base + o_ms);
+    t->moe_plan = reinterpret_cast<int32_t*>(base + o_mp); t->moe_groups = reinterpret_cast<int32_t*>(base + o_mg);
+    t->moe_hp = base + o_mh; t->moe_act = base + o_ma; t->moe_y = base + o_my;
+  }
 
   std::vector<int32_t> ints;
   ints.reserve(n_int);
@@ -665,6 +721,24 @@ void fp_prefill_end(fp_prefill* t) {
     m->live_tasks--;
   }
   delete t;
+}
+
+fp_status fp_prefill_moe_routing(fp_prefill* t, int32_t layer, int32_t* ids_out, float* weights_out) {
+  if (!t || !ids_out || !weights_out) return fail(FP_ERR_INVALID, "fp_prefill_moe_routing: null argument");
+  const fp_shape& sh = t->model->shape;
+  if (sh.n_experts == 0) return fail(FP_ERR_INVALID, "fp_prefill_moe_routing: dense model");
+  if (layer < 0 || layer >= sh.n_layers) return fail(FP_ERR_INVALID, "fp_prefill_moe_routing: layer out of range");
+  int32_t cl = 0, co = 0;
+  (void)fp_prefill_cursor(t, &cl, &co);
+  if (cl * FP_OPS_PER_LAYER + co <= layer * FP_OPS_PER_LAYER + 6)
+    return fail(FP_ERR_STATE, "fp_prefill_moe_routing: that layer's gate operator has not run yet");
+  const size_t n = (size_t)t->n_tokens * sh.top_k;
+  FP_HIP(hipStreamSynchronize(t->model->stream));
+  if (n) {
+    FP_HIP(hipMemcpy(ids_out, t->moe_ids + (size_t)layer * n, n * 4, hipMemcpyDeviceToDevice));
+    FP_HIP(hipMemcpy(weights_out, t->moe_wts + (size_t)layer * n, n * 4, hipMemcpyDeviceToDevice));
+  }
+  return FP_OK;
 }
 
 fp_status fp_op_gemm(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,

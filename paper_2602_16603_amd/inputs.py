@@ -34,6 +34,8 @@ class ShapeSpec:
     ffn: int
     rms_eps: float
     rope_theta: float
+    n_experts: int = 0          # > 0: mixture-of-experts FFN, `ffn` is one expert's width
+    top_k: int = 0
 
     @property
     def qkv_width(self) -> int:
@@ -41,7 +43,8 @@ class ShapeSpec:
 
     def params_per_layer(self) -> int:
         d = self.hidden
-        return d * self.qkv_width + self.n_q_heads * self.head_dim * d + 3 * d * self.ffn
+        ffn = 3 * d * self.ffn * max(1, self.n_experts) + d * self.n_experts
+        return d * self.qkv_width + self.n_q_heads * self.head_dim * d + ffn
 
     def with_layers(self, n_layers: int) -> "ShapeSpec":
         return replace(self, n_layers=n_layers)
@@ -50,6 +53,10 @@ class ShapeSpec:
 TINY = ShapeSpec(2, 256, 4, 2, 64, 704, 1e-5, 10000.0)
 LLAMA3_8B = ShapeSpec(32, 4096, 32, 8, 128, 14336, 1e-5, 500000.0)
 QWEN25_32B = ShapeSpec(64, 5120, 40, 8, 128, 27648, 1e-5, 1000000.0)
+# Mixture-of-experts shapes (Section 7): a tiny one for element-by-element parity and the shape of
+# the 30B-A3B model the paper evaluates (128 experts of width 768, 8 per token).
+TINY_MOE = ShapeSpec(2, 256, 4, 2, 64, 128, 1e-5, 10000.0, n_experts=8, top_k=2)
+QWEN3_30B_A3B = ShapeSpec(48, 2048, 32, 4, 128, 768, 1e-6, 1000000.0, n_experts=128, top_k=8)
 
 CONFIGS: Dict[str, dict] = {
     "cfg1": dict(shape=TINY, seed=1, lengths=[256]),
@@ -86,14 +93,23 @@ def make_layer_weights(shape: ShapeSpec, layer: int, seed: int, dtype: torch.dty
     w_gate_up [2F, d], w_down [d, F]."""
     d, f = shape.hidden, shape.ffn
     base = seed * 1000003 + layer * 101
-    return {
+    out = {
         "attn_norm": torch.ones(d, dtype=dtype, device=device),
         "w_qkv": normal_tensor((shape.qkv_width, d), 0.02, base + 1, dtype, device),
         "w_o": normal_tensor((d, shape.n_q_heads * shape.head_dim), 0.02, base + 2, dtype, device),
         "mlp_norm": torch.ones(d, dtype=dtype, device=device),
-        "w_gate_up": normal_tensor((2 * f, d), 0.02, base + 3, dtype, device),
-        "w_down": normal_tensor((d, f), 0.02, base + 4, dtype, device),
     }
+    if shape.n_experts:
+        # Mixture of experts: w_router [E, d] (wider spread, so that the selection is not a
+        # near-tie everywhere), w_gate_up [E, 2F, d], w_down [E, d, F].
+        e = shape.n_experts
+        out["w_router"] = normal_tensor((e, d), 0.2, base + 5, dtype, device)
+        out["w_gate_up"] = normal_tensor((e, 2 * f, d), 0.02, base + 3, dtype, device)
+        out["w_down"] = normal_tensor((e, d, f), 0.02, base + 4, dtype, device)
+    else:
+        out["w_gate_up"] = normal_tensor((2 * f, d), 0.02, base + 3, dtype, device)
+        out["w_down"] = normal_tensor((d, f), 0.02, base + 4, dtype, device)
+    return out
 
 
 def make_weights(shape: ShapeSpec, seed: int, dtype: torch.dtype, device="cpu"

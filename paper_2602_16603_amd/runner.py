@@ -123,6 +123,15 @@ class PrefillTask:
             B.fp_prefill_kv_gather(self.handle, layer, seq, k.data_ptr(), v.data_ptr())
         return k, v
 
+    def moe_routing(self, layer: int) -> Tuple[torch.Tensor, torch.Tensor]:
+        """(expert ids [T, top_k] int32, weights [T, top_k] fp32) chosen by layer `layer`'s router."""
+        k = self.model.spec.top_k
+        ids = torch.empty((self.cu[-1], k), dtype=torch.int32, device="cuda")
+        wts = torch.empty((self.cu[-1], k), dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        B.fp_prefill_moe_routing(self.handle, layer, ids.data_ptr(), wts.data_ptr())
+        return ids, wts
+
     def block_tables(self) -> np.ndarray:
         return B.fp_prefill_block_tables(self.handle, len(self.lengths))
 

@@ -424,3 +424,14 @@ def test_moe_matches_python_loops_on_tiny_inputs():
             want = [want[c] + prob[e] / norm * y[c] for c in range(4)]
         assert torch.allclose(got[t], torch.tensor(want, dtype=torch.float64), rtol=1e-10, atol=1e-12)
         assert abs(float(wts[t].sum()) - 1.0) < 1e-12 and len(set(order)) == k
+
+
+def test_moe_forcing_the_oracles_own_selection_changes_nothing():
+    h, wr, wgu, wd = _moe_inputs()
+    ids, wts = O.moe_route(h, wr, 2)
+    assert torch.allclose(O.moe_mlp(h, wr, wgu, wd, 2, forced_ids=ids), O.moe_mlp(h, wr, wgu, wd, 2), rtol=1e-13, atol=1e-13)
+    assert torch.allclose(O.moe_weights_for(h, wr, ids), wts, rtol=1e-13, atol=1e-13)
+    assert float(O.moe_selection_shortfall(h, wr, ids, 2).max()) == 0.0
+    worse = ids.clone()
+    worse[:, 1] = torch.tensor([[e for e in range(4) if e not in row.tolist()][0] for row in ids])   # swap in an unselected expert
+    assert float(O.moe_selection_shortfall(h, wr, worse, 2).min()) > 0.0

@@ -42,7 +42,8 @@ def fro_rel_err(got: torch.Tensor, ref: torch.Tensor) -> float:
 
 def oracle_shape(spec) -> O.Shape:
     return O.Shape(spec.n_layers, spec.hidden, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
-                   spec.ffn, spec.rms_eps, spec.rope_theta)
+                   spec.ffn, spec.rms_eps, spec.rope_theta, getattr(spec, "n_experts", 0),
+                   getattr(spec, "top_k", 0))
 
 
 def oracle_layers(weights: Sequence[Dict[str, torch.Tensor]]) -> List[O.LayerWeights]:
