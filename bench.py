@@ -29,8 +29,11 @@ def op_flops(spec, lengths):
     t = sum(lengths)
     d, f, hq, dh = spec.hidden, spec.ffn, spec.n_q_heads, spec.head_dim
     attn = sum(2.0 * hq * dh * n * (n + 1) for n in lengths)
-    return [0.0, 2.0 * t * d * spec.qkv_width, 0.0, attn, 2.0 * t * hq * dh * d, 0.0,
-            2.0 * t * d * 2 * f, 0.0, 2.0 * t * f * d]
+    if getattr(spec, "n_experts", 0):      # gate (router) | experts: gate/up | experts: down, top_k experts per token
+        ffn = [2.0 * t * d * spec.n_experts, 2.0 * t * spec.top_k * d * 2 * f, 2.0 * t * spec.top_k * f * d]
+    else:
+        ffn = [2.0 * t * d * 2 * f, 0.0, 2.0 * t * f * d]
+    return [0.0, 2.0 * t * d * spec.qkv_width, 0.0, attn, 2.0 * t * hq * dh * d, 0.0] + ffn
 
 
 def cpu_baseline(spec, seed, sample_tokens, sample_layers):
@@ -311,7 +314,7 @@ def main() -> int:
     dom_avg_ms = statistics.fmean(dom_ms)
     achieved = dom_flops / (dom_avg_ms * 1e-3) / 1e12
     per_op = {}
-    for o, name in enumerate(B.OP_NAMES):
+    for o, name in enumerate(B.MOE_OP_NAMES if getattr(spec, "n_experts", 0) else B.OP_NAMES):
         avg = statistics.fmean(op_ms[o])
         per_op[name] = {"ms": round(avg, 4)}
         if per_layer[o] > 0:

@@ -71,14 +71,19 @@ void launch_kv_gather(int dtype, const void* k_pool, const void* v_pool, void* k
                       int len, const Geometry& g, int layer, const int32_t* table_dev,
                       hipStream_t s);
 
-// Mixture-of-experts FFN (bf16 path).  plan = device int32 [3 * n_experts]: counts | row offsets |
-// cursors; groups = device int32 [1 + 3 * (n_tokens*top_k/256 + n_experts)]: the row-tile table
-// launch_gemm_grouped reads.  counts must be zero before launch_moe_route.
+// Mixture-of-experts FFN (bf16 path).  plan = device int32 [n_experts] (row offset of every
+// expert); block_counts = device int32 [moe_route_blocks(T)][n_experts]; slot_of = device int32
+// [T*top_k] (rank inside the route workgroup after launch_moe_route, final row after
+// launch_moe_gather); groups = device int32 [1 + 3 * (T*top_k/256 + n_experts)]: the row-tile
+// table launch_gemm_grouped reads.
 void launch_fill_zero(void* p, int64_t n_dwords, hipStream_t s);
-void launch_moe_route(const float* logits, int32_t* ids, float* wts, int32_t* plan, int32_t* groups,
-                      int64_t n_tokens, int n_experts, int top_k, hipStream_t s);
-void launch_moe_gather(const void* h, void* hp, const int32_t* ids, int32_t* plan, int32_t* slot_of,
-                       int64_t n_tokens, int top_k, int n_experts, int d, hipStream_t s);
+int moe_route_blocks(int64_t n_tokens);
+void launch_moe_route(const float* logits, int32_t* ids, float* wts, int32_t* slot_of, int32_t* plan,
+                      int32_t* block_counts, int32_t* groups, int64_t n_tokens, int n_experts, int top_k,
+                      hipStream_t s);
+void launch_moe_gather(const void* h, void* hp, const int32_t* ids, const int32_t* plan,
+                       const int32_t* block_counts, int32_t* slot_of, int64_t n_tokens, int top_k,
+                       int n_experts, int d, hipStream_t s);
 void launch_moe_combine(float* x, const void* y, const int32_t* slot_of, const float* wts,
                         int64_t n_tokens, int top_k, int d, hipStream_t s);
 

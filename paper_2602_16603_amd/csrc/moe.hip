@@ -21,107 +21,146 @@ void launch_fill_zero(void* p, int64_t n_dwords, hipStream_t s) {
   fill_zero_kernel<<<dim3((unsigned)((n_dwords + 255) / 256)), 256, 0, s>>>((uint32_t*)p, n_dwords);
 }
 
-// One wave per token: probabilities, top_k selection, renormalised weights, per-expert counts.
-// n_experts <= 256 (lane l holds experts l, l+64, l+128, l+192), top_k <= 8.
-__global__ __launch_bounds__(256) void moe_route_kernel(const float* __restrict__ logits,
-                                                        int32_t* __restrict__ ids,
-                                                        float* __restrict__ wts,
-                                                        int32_t* __restrict__ counts, int n_tokens,
-                                                        int n_experts, int top_k) {
-  const int lane = threadIdx.x & 63;
-  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (t >= n_tokens) return;
-  float p[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int e = lane + 64 * i;
-    p[i] = e < n_experts ? logits[(int64_t)t * n_experts + e] : -INFINITY;
-  }
-  float mx = fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3]));
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-  float sum = 0.f;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    p[i] = lane + 64 * i < n_experts ? expf(p[i] - mx) : -1.0f;   // -1: never selected
-    sum += fmaxf(p[i], 0.f);
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-  const float inv = 1.0f / sum;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) p[i] = p[i] >= 0.f ? p[i] * inv : -1.0f;
+// Router: one wave per token (16 waves per workgroup, 4 tokens per wave): probabilities, top_k
+// selection, renormalised weights.  n_experts <= 256 (lane l holds experts l, l+64, l+128, l+192),
+// top_k <= 8.  Every chosen (token, expert) pair also takes a rank among the workgroup's pairs of
+// that expert (an LDS counter), and the workgroup leaves its per-expert counts in
+// block_counts[block][expert]: the row plan below needs no global atomics (65536 of them on 128
+// addresses cost more than the rest of the operator).
+constexpr int kRouteTokensPerBlock = 64;
 
-  float chosen_p[8];
-  int chosen_e[8];
-  float total = 0.f;
-  for (int j = 0; j < top_k; ++j) {
-    float bv = p[0];
-    int be = lane;
+__global__ __launch_bounds__(1024) void moe_route_kernel(const float* __restrict__ logits,
+                                                         int32_t* __restrict__ ids,
+                                                         float* __restrict__ wts,
+                                                         int32_t* __restrict__ rank_in_block,
+                                                         int32_t* __restrict__ block_counts,
+                                                         int n_tokens, int n_experts, int top_k) {
+  __shared__ int hist[256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+  __syncthreads();
+  for (int q = 0; q < 4; ++q) {
+    const int t = blockIdx.x * kRouteTokensPerBlock + wave * 4 + q;
+    if (t >= n_tokens) break;                       // wave-uniform
+    float p[4];
 #pragma unroll
-    for (int i = 1; i < 4; ++i)
-      if (p[i] > bv) { bv = p[i]; be = lane + 64 * i; }          // own experts ascend with i: ties keep the lower
+    for (int i = 0; i < 4; ++i) {
+      const int e = lane + 64 * i;
+      p[i] = e < n_experts ? logits[(int64_t)t * n_experts + e] : -INFINITY;
+    }
+    float mx = fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3]));
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const float ov = __shfl_xor(bv, o);
-      const int oe = __shfl_xor(be, o);
-      if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      p[i] = lane + 64 * i < n_experts ? expf(p[i] - mx) : -1.0f;   // -1: never selected
+      sum += fmaxf(p[i], 0.f);
     }
-    chosen_p[j] = bv;
-    chosen_e[j] = be;
-    total += bv;
-    if ((be & 63) == lane) p[be >> 6] = -1.0f;                    // taken
-  }
-  if (lane == 0) {
-    const float norm = 1.0f / total;
-    for (int j = 0; j < top_k; ++j) {
-      ids[(int64_t)t * top_k + j] = chosen_e[j];
-      wts[(int64_t)t * top_k + j] = chosen_p[j] * norm;
-      atomicAdd(&counts[chosen_e[j]], 1);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p[i] = p[i] >= 0.f ? p[i] * inv : -1.0f;
+
+    float chosen_p[8];
+    int chosen_e[8];
+    float total = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (j < top_k) {
+        float bv = p[0];
+        int be = lane;
+#pragma unroll
+        for (int i = 1; i < 4; ++i)
+          if (p[i] > bv) { bv = p[i]; be = lane + 64 * i; }        // own experts ascend with i: ties keep the lower
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+          const float ov = __shfl_xor(bv, o);
+          const int oe = __shfl_xor(be, o);
+          if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+        }
+        chosen_p[j] = bv;
+        chosen_e[j] = be;
+        total += bv;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (be == lane + 64 * i) p[i] = -1.0f;                    // taken
+      }
+    }
+    if (lane == 0) {
+      const float norm = 1.0f / total;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (j < top_k) {
+          ids[(int64_t)t * top_k + j] = chosen_e[j];
+          wts[(int64_t)t * top_k + j] = chosen_p[j] * norm;
+          rank_in_block[(int64_t)t * top_k + j] = atomicAdd(&hist[chosen_e[j]], 1);
+        }
     }
   }
+  __syncthreads();
+  if (threadIdx.x < n_experts) block_counts[(int64_t)blockIdx.x * n_experts + threadIdx.x] = hist[threadIdx.x];
 }
 
-// One thread: per-expert row offsets, the grouped GEMMs' row-tile table, cursors reset.
-//   plan[0 .. E)      counts (input)     plan[E .. 2E)  offsets     plan[2E .. 3E)  cursors
-//   groups[0] = row tiles, then {expert, first row, rows} per tile (256-row tiles)
-__global__ void moe_plan_kernel(int32_t* __restrict__ plan, int32_t* __restrict__ groups, int n_experts) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  int offset = 0, n = 0;
-  for (int e = 0; e < n_experts; ++e) {
-    const int c = plan[e];
-    plan[n_experts + e] = offset;
-    plan[2 * n_experts + e] = 0;
-    for (int m = 0; m < c; m += 256) {
+// One workgroup: per-expert totals and row offsets, the route workgroups' counts turned into
+// their first row inside each expert's range (in place), and the grouped GEMMs' row-tile table.
+//   plan[0 .. E) offsets;   groups[0] = row tiles, then {expert, first row, rows} per 256-row tile
+__global__ __launch_bounds__(256) void moe_plan_kernel(int32_t* __restrict__ plan,
+                                                       int32_t* __restrict__ block_counts,
+                                                       int32_t* __restrict__ groups, int n_experts,
+                                                       int n_blocks) {
+  __shared__ int s_cnt[256], s_off[257], s_tile[257];
+  const int e = threadIdx.x;
+  int total = 0;
+  if (e < n_experts)
+    for (int b = 0; b < n_blocks; ++b) {
+      const int c = block_counts[(int64_t)b * n_experts + e];
+      block_counts[(int64_t)b * n_experts + e] = total;
+      total += c;
+    }
+  s_cnt[e] = total;
+  __syncthreads();
+  if (e == 0) {                                   // 256 LDS steps: cheaper than a parallel scan is worth
+    int off = 0, tiles = 0;
+    for (int i = 0; i < n_experts; ++i) {
+      s_off[i] = off;
+      s_tile[i] = tiles;
+      off += s_cnt[i];
+      tiles += (s_cnt[i] + 255) >> 8;
+    }
+    groups[0] = tiles;
+  }
+  __syncthreads();
+  if (e < n_experts) {
+    plan[e] = s_off[e];
+    const int c = s_cnt[e];
+    int n = s_tile[e];
+    for (int m = 0; m < c; m += 256, ++n) {
       groups[1 + 3 * n] = e;
-      groups[2 + 3 * n] = offset + m;
+      groups[2 + 3 * n] = s_off[e] + m;
       groups[3 + 3 * n] = min(256, c - m);
-      ++n;
     }
-    offset += c;
   }
-  groups[0] = n;
 }
 
-// One wave per (token, choice): take the next free row of the expert's range and copy the
-// token's activations there.
+// One wave per (token, choice): the pair's row = expert's offset + its route workgroup's first
+// row for that expert + its rank there; copy the token's activations into that row.
 __global__ __launch_bounds__(256) void moe_gather_kernel(const bf16* __restrict__ h,
                                                          bf16* __restrict__ hp,
                                                          const int32_t* __restrict__ ids,
-                                                         int32_t* __restrict__ plan,
+                                                         const int32_t* __restrict__ plan,
+                                                         const int32_t* __restrict__ block_counts,
                                                          int32_t* __restrict__ slot_of, int n_pairs,
                                                          int top_k, int n_experts, int d) {
   const int lane = threadIdx.x & 63;
   const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (pair >= n_pairs) return;
-  int slot = 0;
-  if (lane == 0) {
-    const int e = ids[pair];
-    slot = plan[n_experts + e] + atomicAdd(&plan[2 * n_experts + e], 1);
-    slot_of[pair] = slot;
-  }
-  slot = __shfl(slot, 0);
-  const u32x4* src = reinterpret_cast<const u32x4*>(h + (int64_t)(pair / top_k) * d);
+  const int token = pair / top_k;
+  const int e = ids[pair];
+  const int slot = plan[e] + block_counts[(int64_t)(token / kRouteTokensPerBlock) * n_experts + e] + slot_of[pair];
+  if (lane == 0) slot_of[pair] = slot;             // the wave has read its rank from this entry above
+  const u32x4* src = reinterpret_cast<const u32x4*>(h + (int64_t)token * d);
   u32x4* dst = reinterpret_cast<u32x4*>(hp + (int64_t)slot * d);
   for (int c = lane; c < d / 8; c += 64) dst[c] = src[c];
 }
@@ -146,18 +185,23 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(float* __restrict__ x,
   Vec8<float>::store(x + t * d + c * 8, acc);
 }
 
-void launch_moe_route(const float* logits, int32_t* ids, float* wts, int32_t* plan, int32_t* groups,
-                      int64_t n_tokens, int n_experts, int top_k, hipStream_t s) {
-  moe_route_kernel<<<dim3((unsigned)((n_tokens + 3) / 4)), 256, 0, s>>>(logits, ids, wts, plan, (int)n_tokens,
-                                                                        n_experts, top_k);
-  moe_plan_kernel<<<1, 64, 0, s>>>(plan, groups, n_experts);
+int moe_route_blocks(int64_t n_tokens) { return (int)((n_tokens + kRouteTokensPerBlock - 1) / kRouteTokensPerBlock); }
+
+void launch_moe_route(const float* logits, int32_t* ids, float* wts, int32_t* slot_of, int32_t* plan,
+                      int32_t* block_counts, int32_t* groups, int64_t n_tokens, int n_experts, int top_k,
+                      hipStream_t s) {
+  const int n_blocks = moe_route_blocks(n_tokens);
+  moe_route_kernel<<<dim3((unsigned)n_blocks), 1024, 0, s>>>(logits, ids, wts, slot_of, block_counts, (int)n_tokens,
+                                                           n_experts, top_k);
+  moe_plan_kernel<<<1, 256, 0, s>>>(plan, block_counts, groups, n_experts, n_blocks);
 }
 
-void launch_moe_gather(const void* h, void* hp, const int32_t* ids, int32_t* plan, int32_t* slot_of,
-                       int64_t n_tokens, int top_k, int n_experts, int d, hipStream_t s) {
+void launch_moe_gather(const void* h, void* hp, const int32_t* ids, const int32_t* plan,
+                       const int32_t* block_counts, int32_t* slot_of, int64_t n_tokens, int top_k,
+                       int n_experts, int d, hipStream_t s) {
   const int64_t pairs = n_tokens * top_k;
-  moe_gather_kernel<<<dim3((unsigned)((pairs + 3) / 4)), 256, 0, s>>>((const bf16*)h, (bf16*)hp, ids, plan, slot_of,
-                                                                      (int)pairs, top_k, n_experts, d);
+  moe_gather_kernel<<<dim3((unsigned)((pairs + 3) / 4)), 256, 0, s>>>((const bf16*)h, (bf16*)hp, ids, plan, block_counts,
+                                                                      slot_of, (int)pairs, top_k, n_experts, d);
 }
 
 void launch_moe_combine(float* x, const void* y, const int32_t* slot_of, const float* wts,

@@ -96,7 +96,7 @@ struct fp_prefill {
   void *h = nullptr, *qkv = nullptr, *o = nullptr, *gu = nullptr, *act = nullptr;
   // mixture-of-experts scratch (device; null for dense models)
   float* moe_logits = nullptr; float* moe_wts = nullptr;
-  int32_t *moe_ids = nullptr, *moe_slot = nullptr, *moe_plan = nullptr, *moe_groups = nullptr;
+  int32_t *moe_ids = nullptr, *moe_slot = nullptr, *moe_plan = nullptr, *moe_groups = nullptr, *moe_blocks = nullptr;
   void *moe_hp = nullptr, *moe_act = nullptr, *moe_y = nullptr;
   int32_t moe_max_row_tiles = 0;
   bool swiglu_fused = false;   // op 6 writes act directly (fused epilogue); op 7 then has no work and gu is not allocated
@@ -129,18 +129,18 @@ fp_status launch_op(fp_prefill* t, int32_t index) {
   const int64_t qd = (int64_t)sh.n_q_heads * sh.head_dim;
   hipStream_t s = m->stream;
   if (sh.n_experts > 0 && op >= 6) {
+    if (T == 0) return FP_OK;
     const int E = sh.n_experts, k = sh.top_k;
     int32_t* ids = t->moe_ids + (int64_t)layer * T * k;      // kept per layer for inspection
     float* wts = t->moe_wts + (int64_t)layer * T * k;
     switch (op) {
       case 6:   // gate: router logits (fp32, accumulated into zeros), selection, row plan
         fp::launch_fill_zero(t->moe_logits, T * E, s);
-        fp::launch_fill_zero(t->moe_plan, E, s);
         fp::launch_gemm(dt, t->h, w.w_router, t->moe_logits, T, E, d, 1, t->splitk, t->splitk_bytes, s);
-        fp::launch_moe_route(t->moe_logits, ids, wts, t->moe_plan, t->moe_groups, T, E, k, s);
+        fp::launch_moe_route(t->moe_logits, ids, wts, t->moe_slot, t->moe_plan, t->moe_blocks, t->moe_groups, T, E, k, s);
         break;
       case 7:   // experts, first half: gather per expert, gate/up projection + SiLU*up
-        fp::launch_moe_gather(t->h, t->moe_hp, ids, t->moe_plan, t->moe_slot, T, k, E, (int)d, s);
+        fp::launch_moe_gather(t->h, t->moe_hp, ids, t->moe_plan, t->moe_blocks, t->moe_slot, T, k, E, (int)d, s);
         fp::launch_gemm_grouped(t->moe_hp, w.w_gate_up, t->moe_act, F, d, 1, t->moe_groups, t->moe_max_row_tiles, s);
         break;
       case 8:   // experts, second half: down projection, weighted sum into the residual stream
@@ -455,7 +455,7 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   t->moe_max_row_tiles = moe ? (int32_t)(pairs / 256 + E) : 0;
   const size_t o_ml = carve(moe ? Tn * E * 4 : 0), o_mw = carve(moe ? pairs * 4 * sh.n_layers : 0),
                o_mi = carve(moe ? pairs * 4 * sh.n_layers : 0), o_ms = carve(moe ? pairs * 4 : 0),
-               o_mp = carve(moe ? 3 * E * 4 : 0), o_mg = carve(moe ? (1 + 3 * (size_t)t->moe_max_row_tiles) * 4 : 0),
+               o_mp = carve(moe ? E * 4 : 0), o_mb = carve(moe ? (size_t)fp::moe_route_blocks(T) * E * 4 : 0), o_mg = carve(moe ? (1 + 3 * (size_t)t->moe_max_row_tiles) * 4 : 0),
                o_mh = carve(moe ? pairs * d * e : 0), o_ma = carve(moe ? pairs * F * e : 0),
                o_my = carve(moe ? pairs * d * e : 0);
   const size_t sk_dense = std::max(fp::gemm_workspace_bytes(sh.dtype, T, 2 * (int64_t)F, (int64_t)d),
@@ -480,7 +480,7 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   if (moe) {
     t->moe_logits = reinterpret_cast<float*>(base + o_ml); t->moe_wts = reinterpret_cast<float*>(base + o_mw);
     t->moe_ids = reinterpret_cast<int32_t*>(base + o_mi); t->moe_slot = reinterpret_cast<int32_t*>(base + o_ms);
-    t->moe_plan = reinterpret_cast<int32_t*>(base + o_mp); t->moe_groups = reinterpret_cast<int32_t*>(base + o_mg);
+    t->moe_plan = reinterpret_cast<int32_t*>(base + o_mp); t->moe_blocks = reinterpret_cast<int32_t*>(base + o_mb); t->moe_groups = reinterpret_cast<int32_t*>(base + o_mg);
     t->moe_hp = base + o_mh; t->moe_act = base + o_ma; t->moe_y = base + o_my;
   }
 
