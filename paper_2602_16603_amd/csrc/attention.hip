@@ -7,6 +7,7 @@
 
 namespace fp {
 
+
 // ------------------------------------------------------------------------------------------
 // bf16 kernel.
 //
@@ -33,7 +34,10 @@ namespace fp {
 //
 // The running maximum is applied lazily: the exponent reference m_use is only moved (and O, l
 // rescaled) when some row's maximum has grown by more than 2^8 since the reference was set, so
-// exp2 arguments stay <= 8 and almost every tile skips the D/32*16 rescale multiplies.
+// exp2 arguments stay <= 8 and almost every tile skips the D/32*16 rescale multiplies.  The
+// query fragments are scaled by log2(e)/sqrt(D) once, and the score MFMAs start from an
+// accumulator holding -m_use instead of zero: they deliver s - m_use, the exp2 argument,
+// directly, which takes one FMA per score out of the VALU-bound softmax.
 //
 // LDS layouts (16-byte chunks).  Measured on gfx950: 64 banks; a ds_read_b128 is served one
 // half-wave after the other, and a half-wave costs max(2, most lanes on one 16-byte bank group)
@@ -173,7 +177,15 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
     const int row = min(wq0 + lq, n_new - 1);
     const bf16* src = qkv + (int64_t)(seq_lo + row) * width + head * D + lh * 8;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(src + kk * 16);
+    for (int kk = 0; kk < KK; ++kk) {
+      // Scores come out of the MFMA already in exp2 units: q is scaled by log2(e)/sqrt(D) here,
+      // once, instead of every score in every tile.
+      const f32x8 q = __builtin_convertvector(*reinterpret_cast<const bf16x8*>(src + kk * 16), f32x8);
+      f32x8 qs;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qs[e] = q[e] * scale_log2;
+      qf[kk] = __builtin_convertvector(qs, bf16x8);
+    }
   }
 
   f32x16 oacc[DB];
@@ -181,15 +193,20 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
   for (int i = 0; i < DB; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
-  float m_use = -INFINITY;      // exponent reference (raw score units)
+  float m_use = -INFINITY;      // exponent reference of this lane's query (exp2 units)
   float l_run = 0.f;            // this lane's half of the row sum
+  // -m_use in all 16 accumulator slots: the score MFMAs start from it, so they deliver s - m_use,
+  // the exp2 argument, directly.  Rewritten only when the reference moves.
+  f32x16 neg_m;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) neg_m[r] = 0.f;
 
   const int wave_q_min = cached + wq0;               // smallest query position of the wave
   const int wave_q_max = cached + wq0 + 31;          // largest
   const int qpos = cached + wq0 + lq;
   const int pi_row = pi_swap23(lq);
   const int k_swz = k_key_of_lane<D>(lq);
-  const float lazy_gap = 8.0f / scale_log2;          // 2^8 of head-room, in raw score units
+  const float lazy_gap = 8.0f;                        // 2^8 of head-room
   const bool wave_valid = wq0 < n_new;
 
   // One tile: scores, softmax, P V from stage (cK, cV); the loader waves then start the DMA of
@@ -205,11 +222,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk)
           kf[kk] = *reinterpret_cast<const bf16x8*>(krow + (((kk * 2 + lh) ^ k_swz) << 3));
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[rb][r] = 0.f;
         __builtin_amdgcn_sched_barrier(0);
+        sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0], neg_m, 0, 0, 0);
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
+        for (int kk = 1; kk < KK; ++kk)
           sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sacc[rb], 0, 0, 0);
       }
       if (key0 + kKT - 1 > wave_q_min) {              // tile straddles the diagonal: mask
@@ -221,6 +237,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
             sacc[rb][r] = key <= qpos ? sacc[rb][r] : -INFINITY;
           }
       }
+      // sacc = s - m_use.  The first tile (m_use = -inf encoded as neg_m = 0) and any tile whose
+      // row maximum exceeds the reference by more than the head-room move the reference.
       float mx = -INFINITY;
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb)
@@ -228,28 +246,33 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
         for (int r = 0; r < 16; r += 2) mx = fmaxf(mx, fmaxf(sacc[rb][r], sacc[rb][r + 1]));
       mx = xhalf_max(mx);
       // Key 0 is visible to every query, so mx is finite from the first tile on.
-      if (__any(mx > m_use + lazy_gap)) {
-        const float m_new = fmaxf(m_use, mx);
-        const float alpha = __builtin_amdgcn_exp2f((m_use - m_new) * scale_log2);
-        m_use = m_new;
+      if (__any(m_use == -INFINITY || mx > lazy_gap)) {
+        const float shift = m_use == -INFINITY ? mx : fmaxf(mx, 0.f);   // new reference - old reference
+        const float base = m_use == -INFINITY ? 0.f : m_use;
+        const float alpha = m_use == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(-shift);
+        m_use = base + shift;
         l_run *= alpha;
 #pragma unroll
         for (int i = 0; i < DB; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sacc[rb][r] -= shift;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) neg_m[r] = -m_use;
       }
-      const float mc = m_use * scale_log2;
       float psum = 0.f;
       bf16x8 pf[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         f32x8 pv;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          pv[e] = __builtin_amdgcn_exp2f(fmaf(sacc[c >> 1][8 * (c & 1) + e], scale_log2, -mc));
-          psum += pv[e];
-        }
+        for (int e = 0; e < 8; ++e) pv[e] = __builtin_amdgcn_exp2f(sacc[c >> 1][8 * (c & 1) + e]);
         pf[c] = __builtin_convertvector(pv, bf16x8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) psum += pv[e];
       }
       l_run += psum;
 #pragma unroll
