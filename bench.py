@@ -22,6 +22,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak (vendor, no sparsity)
+HBM_PEAK_GBPS = 8000.0             # MI355X HBM3E peak (vendor)
+MEASURED_MFMA_TFLOPS = 1890.0      # sustained rate of a register-only MFMA loop with random operands on this machine
 
 
 def op_flops(spec, lengths):
@@ -313,12 +315,38 @@ def main() -> int:
     dom_flops = sum(per_layer[o] for o in dom_ops) / len(dom_ops)      # mean per launch
     dom_avg_ms = statistics.fmean(dom_ms)
     achieved = dom_flops / (dom_avg_ms * 1e-3) / 1e12
+    # Algorithmic HBM bytes of the bandwidth-bound operators (fp32 residual in, bf16 out for the
+    # norms; RoPE reads q,k,v and writes q,k back plus k,v into the cache).
+    kvw = spec.n_kv_heads * spec.head_dim
+    hbm_bytes = {0: total * spec.hidden * 6.0, 5: total * spec.hidden * 6.0,
+                 2: total * 2.0 * (spec.qkv_width + (spec.n_q_heads * spec.head_dim + kvw) + 2 * kvw)}
     per_op = {}
     for o, name in enumerate(B.MOE_OP_NAMES if getattr(spec, "n_experts", 0) else B.OP_NAMES):
         avg = statistics.fmean(op_ms[o])
         per_op[name] = {"ms": round(avg, 4)}
         if per_layer[o] > 0:
             per_op[name]["tflops"] = round(per_layer[o] / (avg * 1e-3) / 1e12, 1)
+            per_op[name]["roof_frac"] = round(per_layer[o] / (avg * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS, 3)
+        elif o in hbm_bytes:
+            per_op[name]["gbps"] = round(hbm_bytes[o] / (avg * 1e-3) / 1e9, 1)
+            per_op[name]["roof_frac"] = round(hbm_bytes[o] / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 3)
+
+    # What the preemption checks cost when no signal ever fires (Section 6.5): the same steps with
+    # a check after every operator (bounded launch-ahead) and with no checks at all, untimed per op.
+    check_overhead = None
+    if args.config == "cfg2" and not args.layers:
+        def plain(mask):
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                task = model.begin(hidden, lengths, boundary_mask=mask)
+                task.run_to_completion()
+                task.end()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t1) / args.steps * 1e3
+        ms_none, ms_every = plain(B.FP_BOUNDARY_NONE), plain(B.FP_BOUNDARY_EVERY_OP)
+        check_overhead = {"ms_per_step_no_checks": round(ms_none, 4), "ms_per_step_check_every_op": round(ms_every, 4),
+                          "ratio": round(ms_every / ms_none, 4)}
 
     # HBM-side bytes per launch of the dominant kernel come from the committed rocprofv3 --pmc
     # summary (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy); null when that file is absent
@@ -339,7 +367,8 @@ def main() -> int:
                                f"{len(lengths)} prompt(s), {total} tokens, 9 ops/layer with a preemption "
                                f"check at every boundary", "seed": seed},
         "tflops": round(tflops, 1), "mfma_frac": round(tflops / BF16_MFMA_PEAK_TFLOPS, 4),
-        "per_op": per_op,
+        "measured_peak_frac": round(tflops / MEASURED_MFMA_TFLOPS, 4),
+        "per_op": per_op, "check_overhead": check_overhead,
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_pp_kernel<3> (gate_up_proj with fused SiLU*up)",
                      "achieved": round(achieved, 1), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
