@@ -101,3 +101,42 @@ def test_qwen3_30b_a3b_shaped_layer_matches_oracle():
     model, task, _, _ = run_and_check(spec, [1500, 548], 53, pool_blocks=256)
     task.end()
     model.close()
+
+
+@pytest.mark.parametrize("lengths", [[3], [0], [1, 0, 2]])
+def test_moe_with_almost_no_tokens(lengths):
+    """Three tokens over eight experts leave most experts without a row (no row tile at all);
+    an empty batch launches nothing."""
+    B, R = _mods()
+    spec = I.TINY_MOE
+    if sum(lengths) == 0:
+        weights = I.make_weights(spec, 54, torch.bfloat16, "cuda")
+        model = R.PrefillModel(spec, weights, B.FP_DTYPE_BF16, 16, 16)
+        task = model.begin(torch.empty((0, spec.hidden), dtype=torch.bfloat16, device="cuda"), lengths)
+        status, _ = task.advance()
+        assert status == B.FP_DONE
+        task.end()
+        model.close()
+        return
+    model, task, _, _ = run_and_check(spec, lengths, 54, pool_blocks=16)
+    task.end()
+    model.close()
+
+
+def test_moe_shape_validation():
+    B, R = _mods()
+    import dataclasses
+    weights = I.make_weights(I.TINY_MOE, 55, torch.bfloat16, "cuda")
+    for bad in (dataclasses.replace(I.TINY_MOE, top_k=0), dataclasses.replace(I.TINY_MOE, top_k=9),
+                dataclasses.replace(I.TINY_MOE, n_experts=12, top_k=2)):
+        with pytest.raises(B.FlowPrefillError):
+            R.PrefillModel(bad, weights, B.FP_DTYPE_BF16, 16, 16)
+    with pytest.raises(B.FlowPrefillError):                       # fp32 debug path has no MoE
+        R.PrefillModel(I.TINY_MOE, I.make_weights(I.TINY_MOE, 55, torch.float32, "cuda"), B.FP_DTYPE_F32, 16, 16)
+    dense = R.PrefillModel(I.TINY, I.make_weights(I.TINY, 55, torch.bfloat16, "cuda"), B.FP_DTYPE_BF16, 16, 16)
+    t = dense.begin(I.make_hidden(4, I.TINY.hidden, 1, torch.bfloat16, "cuda"), [4])
+    t.run_to_completion()
+    with pytest.raises(B.FlowPrefillError):                       # dense model has no routing to report
+        t.moe_routing(0)
+    t.end()
+    dense.close()
