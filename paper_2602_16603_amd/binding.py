@@ -79,6 +79,7 @@ _SIGS = {
     "fp_sched_retire": (C.c_int, [_P, C.c_int64]),
     "fp_sched_round": (C.c_int, [_P, C.c_double, _P]),
     "fp_sched_predict": (C.c_double, [_P, C.c_int64]),
+    "fp_diag_mfma_ceiling": (C.c_int, [C.c_int32, _P, C.POINTER(C.c_double)]),
     "fp_last_error": (C.c_char_p, []),
     "fp_version": (C.c_char_p, []),
 }
@@ -252,6 +253,12 @@ def fp_op_rmsnorm(dtype: int, x_f32: int, gain: int, out: int, t: int, d: int, e
 
 def fp_prefill_moe_routing(task: int, layer: int, ids_out: int, weights_out: int) -> None:
     _check(lib.fp_prefill_moe_routing(_P(task), layer, _P(ids_out), _P(weights_out)), "fp_prefill_moe_routing")
+
+
+def fp_diag_mfma_ceiling(milliseconds: int = 200, hip_stream: int = 0) -> float:
+    out = C.c_double()
+    _check(lib.fp_diag_mfma_ceiling(milliseconds, _P(hip_stream), C.byref(out)), "fp_diag_mfma_ceiling")
+    return out.value
 
 
 def fp_op_silu_mul(dtype: int, gu: int, out: int, t: int, f: int, hip_stream: int = 0) -> None:

@@ -87,6 +87,9 @@ void launch_moe_gather(const void* h, void* hp, const int32_t* ids, const int32_
 void launch_moe_combine(float* x, const void* y, const int32_t* slot_of, const float* wts,
                         int64_t n_tokens, int top_k, int d, hipStream_t s);
 
+// Register-only MFMA loop (diagnostic); sink = device float[blocks * 512]; returns FLOPs per launch.
+double launch_mfma_ceiling(float* sink, int blocks, int iters, hipStream_t s);
+
 // Sets the calling thread's fp_last_error() text (for translation units other than the runtime).
 void set_last_error(const char* message);
 

@@ -741,6 +741,43 @@ fp_status fp_prefill_moe_routing(fp_prefill* t, int32_t layer, int32_t* ids_out,
   return FP_OK;
 }
 
+fp_status fp_diag_mfma_ceiling(int32_t milliseconds, void* hip_stream, double* tflops_out) {
+  if (!tflops_out || milliseconds <= 0 || milliseconds > 5000)
+    return fail(FP_ERR_INVALID, "fp_diag_mfma_ceiling: milliseconds must be in 1..5000");
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  int cus = 0, dev = 0;
+  FP_HIP(hipGetDevice(&dev));
+  FP_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  const int blocks = cus > 0 ? cus : 256;               // one workgroup of 8 waves per CU
+  float* sink = nullptr;
+  FP_HIP(hipMalloc(&sink, (size_t)blocks * 512 * sizeof(float)));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  fp_status st = FP_OK;
+  double best = 0.0;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) st = fail(FP_ERR_DEVICE, "event creation failed");
+  // 20000 iterations of 8 MFMAs are ~2.7 ms at full rate; repeat until the time budget is used
+  // (the clock settles under load) and report the last launch.
+  const int iters = 20000;
+  float total_ms = 0.f;
+  (void)fp::launch_mfma_ceiling(sink, blocks, 100, s);  // warm-up
+  while (st == FP_OK && total_ms < (float)milliseconds) {
+    (void)hipEventRecord(e0, s);
+    const double flops = fp::launch_mfma_ceiling(sink, blocks, iters, s);
+    (void)hipEventRecord(e1, s);
+    if (hipEventSynchronize(e1) != hipSuccess) { st = fail(FP_ERR_DEVICE, "mfma ceiling launch failed"); break; }
+    float ms = 0.f;
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    if (ms <= 0.f) { st = fail(FP_ERR_DEVICE, "mfma ceiling: no time measured"); break; }
+    total_ms += ms;
+    best = flops / (ms * 1e-3) / 1e12;
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(sink);
+  if (st == FP_OK) *tflops_out = best;
+  return st;
+}
+
 fp_status fp_op_gemm(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
                      int64_t k, int32_t residual, void* hip_stream) {
   if (!a || !w || !c || m <= 0 || n <= 0 || k <= 0 || (k % 8) || (n % 8) || m > INT32_MAX ||

@@ -120,3 +120,13 @@ def test_bad_sizes_are_rejected_not_launched():
         B.fp_op_gemm(1, a.data_ptr(), a.data_ptr(), a.data_ptr(), 0, 8, 8, False)
     with pytest.raises(B.FlowPrefillError):
         B.fp_op_rmsnorm(1, a.data_ptr(), a.data_ptr(), a.data_ptr(), 1, 12, 1e-5)
+
+
+def test_mfma_ceiling_diagnostic_reports_a_plausible_rate():
+    """The register-only MFMA loop cannot beat the vendor's dense bf16 peak and, on an idle chip,
+    does not fall below a third of it."""
+    B = _binding()
+    rate = B.fp_diag_mfma_ceiling(100)
+    assert 800.0 < rate < 2600.0
+    with pytest.raises(B.FlowPrefillError):
+        B.fp_diag_mfma_ceiling(0)
