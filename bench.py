@@ -156,7 +156,7 @@ def preemption_workload(seconds: float, seed: int = 4):
     return result
 
 
-def slo_workload(seconds: float, points, seed: int = 6, token_budget: int = 4096):
+def slo_workload(seconds: float, points, seed: int = 6, token_budget: int = 4096, model_name: str = "8b"):
     """Multi-SLO serving on the 32-layer 8B shape (Section 6.2's experiment on a synthetic stand-in
     for its trace): Poisson arrivals of the four request classes of Table 1 with the TTFT SLOs of
     Table 2, scheduled by the native event-driven scheduler.  Systems compared: S-EDF + SLO-aware
@@ -168,7 +168,8 @@ def slo_workload(seconds: float, points, seed: int = 6, token_budget: int = 4096
     import torch
     from paper_2602_16603_amd import binding as B, eventloop as E, inputs as I, runner as R
 
-    spec = I.CONFIGS["cfg4"]["shape"]
+    # "8b": the dense 32-layer 8B shape of Section 6.2; "moe": the 48-layer 30B-A3B shape of Section 7.
+    spec = I.CONFIGS["cfg4"]["shape"] if model_name == "8b" else I.QWEN3_30B_A3B
     max_n = 32768
     weights = I.make_weights(spec, seed, torch.bfloat16, "cuda")
     model = R.PrefillModel(spec, weights, B.FP_DTYPE_BF16, kv_num_blocks=(1 << 20) // 16, max_position=max_n)
@@ -188,7 +189,7 @@ def slo_workload(seconds: float, points, seed: int = 6, token_budget: int = 4096
             best = dt if best is None else min(best, dt)
         prof_t.append(best)
     coef = [float(c) for c in np.polyfit(np.asarray(prof_n, dtype=np.float64), np.asarray(prof_t), 2)[::-1]]
-    result = {"workload": f"{spec.n_layers}-layer 8B shape; request classes and shares of Table 1, TTFT SLOs of "
+    result = {"workload": f"{spec.n_layers}-layer {'8B' if model_name == '8b' else '30B-A3B mixture-of-experts'} shape; request classes and shares of Table 1, TTFT SLOs of "
                           f"Table 2 (Llama3-8B row); Poisson arrivals for {seconds:g} s per point; token budget G = {token_budget}",
               "ttft_fit_seconds": {"coef_c0_c1_c2": coef, "profile_tokens": prof_n,
                                    "profile_seconds": [round(t, 5) for t in prof_t]},
@@ -241,6 +242,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override layer count (exploration only)")
     ap.add_argument("--slo-seconds", type=float, default=4.0,
                     help="arrival window of each (system, rate) point of the multi-SLO scheduling workload; 0 skips it")
+    ap.add_argument("--slo-model", default="8b", choices=["8b", "moe"],
+                    help="model of the scheduling workload: the dense 8B shape or the 30B-A3B mixture-of-experts shape")
     ap.add_argument("--slo-points", default="32:1,24:0.2",
                     help="rate:slo_scale points of that workload (requests per second : factor on Table 2's SLOs)")
     ap.add_argument("--preempt-seconds", type=float, default=2.0,
@@ -388,7 +391,8 @@ def main() -> int:
         out["preemption"] = preemption_workload(args.preempt_seconds)
     if args.slo_seconds > 0 and args.config == "cfg2" and not args.layers:
         out["slo_scheduling"] = slo_workload(
-            args.slo_seconds, [tuple(float(v) for v in x.split(":")) for x in args.slo_points.split(",")])
+            args.slo_seconds, [tuple(float(v) for v in x.split(":")) for x in args.slo_points.split(",")],
+            model_name=args.slo_model)
     print(json.dumps(out))
     return 0
 
