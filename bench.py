@@ -313,7 +313,7 @@ def main() -> int:
     step_flops = sum(per_layer) * spec.n_layers
     tflops = step_flops / (elapsed / args.steps) / 1e12
 
-    # Dominant kernel: gemm_bf16_pp_kernel<3>, the ping-pong bf16 MFMA GEMM with the SwiGLU
+    # Dominant kernel: gemm_bf16_w4_kernel<3>, the one-wave-per-SIMD bf16 MFMA GEMM with the SwiGLU
     # epilogue (the gate_up_proj launch, one per layer: 47% of a layer's FLOPs, 39% of its time).
     dom_ops = (6,)
     dom_ms = [ms for o in dom_ops for ms in op_ms[o]]
@@ -357,7 +357,7 @@ def main() -> int:
     # summary (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy); null when that file is absent
     # or describes another workload.
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "gemm_bf16_pp_cfg2_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "gemm_bf16_w4_cfg2_traffic.json")
     if args.config == "cfg2" and not args.layers and os.path.exists(tpath):
         with open(tpath) as fh:
             traffic = json.load(fh).get("hbm_bytes_per_launch")
@@ -374,7 +374,7 @@ def main() -> int:
         "tflops": round(tflops, 1), "mfma_frac": round(tflops / BF16_MFMA_PEAK_TFLOPS, 4),
         "mfma_ceiling_tflops": round(mfma_ceiling, 1), "measured_peak_frac": round(tflops / mfma_ceiling, 4),
         "per_op": per_op, "check_overhead": check_overhead,
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_pp_kernel<3> (gate_up_proj with fused SiLU*up)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_w4_kernel<3> (gate_up_proj with fused SiLU*up)",
                      "achieved": round(achieved, 1), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
                      "avg_launch_ms": round(dom_avg_ms, 4), "flops_per_launch": dom_flops},

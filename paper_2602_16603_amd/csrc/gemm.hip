@@ -165,106 +165,87 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16* _
 }
 
 // ------------------------------------------------------------------------------------------
-// Ping-pong bf16 MFMA GEMM (the fast path; K % 64 == 0).
+// bf16 MFMA GEMM, one wave per SIMD (the fast path; K % 64 == 0).
 //
-// 256x256 output tile, K consumed 64 at a time, 512 threads = 8 waves.  The hardware places the
-// waves of a workgroup round-robin on the CU's four SIMDs, so waves w and w+4 share a SIMD.  The
-// two wave groups {0..3} and {4..7} run the same loop half an iteration apart: while one group
-// issues its 32 MFMAs from registers ("compute phase"), the other pulls its MFMA operands for
-// the same k-tile out of LDS ("memory phase"); one s_barrier ends every phase.  The matrix pipe
-// of each SIMD therefore always has a wave with all operands resident, independent of how the
-// compiler schedules inside a phase.
+// 256x256 output tile, K consumed 64 at a time, 256 threads = 4 waves, one per SIMD, each with the
+// whole 512-register budget: a wave owns a 128x128 block of the tile, 4x4 accumulators of 32x32 =
+// 256 accumulator registers.  The wave's instruction stream is software-pipelined by k-step (16 of
+// K = 16 MFMAs = 512 matrix-pipe cycles): between the MFMAs of one k-step sit the 8 LDS fragment
+// reads of the next one and the wave's share of the global loads, one of each per two MFMAs, so
+// the matrix pipe always has its next instruction queued; one s_barrier per k-tile.  The loop
+// body is straight-line code on purpose: the compiler keeps the 256 accumulators in place in the
+// accumulation registers only while no control flow crosses them, so "nothing left to fetch" is
+// expressed through an empty buffer descriptor, never through a branch.
 //
 // Global -> LDS goes through the DMA path (buffer_load_dwordx4 ... lds: no VGPR staging, no
 // ds_write).  A DMA instruction writes lane i's 16 bytes at base + 16*i, i.e. one wave fills
 // eight consecutive 128-byte LDS rows; the LDS swizzle is obtained by permuting which 16-byte
-// global chunk each lane fetches.  Two LDS stages (A and B, 32 KB each per stage).  Group 1
-// does all the loading: during its compute phase of k-tile t -- the first moment at which both
-// groups have finished reading stage t%2 -- it refills that stage with k-tile t+2, one DMA
-// instruction per two MFMAs, and awaits it at the end of its next memory phase, i.e. before the
-// barrier that lets group 0 start reading k-tile t+2.  Stages are separate __shared__ arrays so
-// that the compiler can tell that DMA in flight to one stage does not alias LDS reads of the
-// other (otherwise it would serialise them with vmcnt(0)).  Operand panels are addressed through
-// raw buffer descriptors sized to the valid rows, so row tails of A and W read as zero.
+// global chunk each lane fetches.  Two LDS stages (A and W, 32 KB each per stage) as four
+// separate __shared__ arrays, so that the compiler can tell that DMA in flight to one stage does
+// not alias LDS reads of the other (otherwise it would serialise them with vmcnt(0)).  Wave w
+// fetches rows [64w, 64w+64) of both operands, 16 instructions per k-tile: the A rows in the
+// k-step after the barrier that frees the stage, the W rows in the next one; the remaining two
+// k-steps give them time to land.  Operand panels are addressed through raw buffer descriptors
+// sized to the valid rows, so row tails of A and W read as zero.
+//
+// L2 warm-up.  The 32 workgroups running on one XCD share operand panels (8 tile rows x 4 tile
+// columns under tile_of_workgroup), run in step, and would all ask the XCD's L2 for the same
+// 128-byte lines within a few hundred cycles: one request misses and every sharer's request
+// queues behind that miss (measured: 480 cycles average L2 read latency in gate_up_proj, 3300
+// cycles per k-tile in down_proj).  Instead each workgroup asks for its share of the lines three
+// k-tiles ahead of the DMA -- every 4th row of its A panel (wave 0) and every 8th row of its W
+// panel (wave 1), the shares rotating with the k-tile -- with a one-dword-per-lane load into a
+// dummy LDS pad, so the DMA requests of all sharers find the line resident (2180-2240 cycles per
+// k-tile for both projections).  The pad load is the last VMEM instruction before the wave's
+// wait, which therefore asks for "all but one" and never blocks on it.
 // ------------------------------------------------------------------------------------------
 constexpr int kWaitVm0 = 0x0F70;   // s_waitcnt vmcnt(0)           (expcnt/lgkmcnt untouched)
+constexpr int kWaitVm1 = 0x0F71;   // s_waitcnt vmcnt(1)
+constexpr int kWaitVm8 = 0x0F78;   // s_waitcnt vmcnt(8)
 constexpr int kWaitLgkm0 = 0xC07F; // s_waitcnt lgkmcnt(0)         (vmcnt/expcnt untouched)
+constexpr int kWarmAhead = 3;      // k-tiles between the L2 warm-up load and the DMA of the same lines
+constexpr uint32_t kOffOutOfRange = 0x80000000u;   // a byte offset no descriptor here covers
 
-struct PpFrags {
-  bf16x8 a[4][4];   // [32-row block][k-step]
-  bf16x8 b[2][4];
+struct W4Frags {     // MFMA operands of one k-step: four 32-row blocks of A and of W
+  bf16x8 a[4];
+  bf16x8 b[4];
 };
 
 // Raw buffer descriptor over `bytes` bytes at `base` (stride 0, 32-bit offsets, reads past the
-// end return zero -- which is how row tails of A and W are zero-filled).
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t pp_panel_rsrc(const void* base, uint32_t bytes) {
+// end return zero -- which is how row tails of A and W are zero-filled -- and writes past the end
+// are dropped).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t panel_rsrc(const void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
-// SPLITW (the fused SwiGLU GEMM): a wave's 64 LDS rows of W are 32 gate rows followed by the 32
-// up rows of the same FFN columns; they come through two descriptors (rw, rw2), each shifted so
-// that the per-lane offsets of instructions 0..3 address the right rows of its panel.
-template <bool SPLITW>
-__device__ __forceinline__ void pp_issue_tile(__amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rw,
-                                              __amdgpu_buffer_rsrc_t rw2, int kbyte,
-                                              const uint32_t (&voff)[8], bf16* sA, bf16* sB, int w4) {
+__device__ __forceinline__ void w4_dma(__amdgpu_buffer_rsrc_t r, bf16* lds_rows, uint32_t voff, int kbyte) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)lds_rows, 16, voff, kbyte, 0, 0);
+}
+
+// One k-step: 16 MFMAs from `cur`; after every pair of them one fragment read of the next k-step
+// into `nxt` (in the order the next k-step first uses them: b0 b1 a0 b2 b3 a1 a2 a3) and, if DMA,
+// one of the wave's 8 DMA instructions for one operand (8 rows of 128 bytes each).
+template <bool DMA>
+__device__ __forceinline__ void w4_block(f32x16 (&acc)[4][4], const W4Frags& cur, W4Frags& nxt,
+                                         const bf16* rA, const bf16* rB, int pch,
+                                         __amdgpu_buffer_rsrc_t rs, bf16* lds_rows,
+                                         const uint32_t (&voff)[8], int kbyte) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int base_row = (w4 * 8 + j) * 8;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(
-        ra, (__attribute__((address_space(3))) void*)(sA + base_row * kBK), 16, voff[j], kbyte, 0, 0);
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(
-        (SPLITW && j >= 4) ? rw2 : rw, (__attribute__((address_space(3))) void*)(sB + base_row * kBK), 16,
-        voff[SPLITW ? (j & 3) : j], kbyte, 0, 0);
+  for (int s = 0; s < 8; ++s) {
+    const int i = s >> 1, j0 = (s & 1) * 2;
+    constexpr int kIsA = 0xE4;
+    constexpr int kIdx = (0 << 0) | (1 << 2) | (0 << 4) | (2 << 6) | (3 << 8) | (1 << 10) | (2 << 12) | (3 << 14);
+    const int idx = (kIdx >> (2 * s)) & 3;
+    if ((kIsA >> s) & 1) nxt.a[idx] = *reinterpret_cast<const bf16x8*>(rA + idx * 32 * kBK + pch);
+    else nxt.b[idx] = *reinterpret_cast<const bf16x8*>(rB + idx * 32 * kBK + pch);
+    acc[i][j0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[j0], cur.a[i], acc[i][j0], 0, 0, 0);
+    acc[i][j0 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[j0 + 1], cur.a[i], acc[i][j0 + 1], 0, 0, 0);
+    if (DMA) w4_dma(rs, lds_rows + s * 8 * kBK, voff[s], kbyte);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-__device__ __forceinline__ void pp_read_frags(const bf16* sA, const bf16* sB, int a_row0,
-                                              int b_row0, int key, int half, PpFrags& f) {
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    const int pch = ((kk * 2 + half) ^ key) << 3;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      f.a[i][kk] = *reinterpret_cast<const bf16x8*>(sA + (a_row0 + i * 32) * kBK + pch);
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-      f.b[j][kk] = *reinterpret_cast<const bf16x8*>(sB + (b_row0 + j * 32) * kBK + pch);
-  }
-}
-
-// Compute phase: the 32 MFMAs of one k-tile.  In the loading group (`load` set, wave-uniform)
-// the 16 DMA instructions of one whole k-tile (8 for A, 8 for W per wave of the group) are
-// slotted in one per two MFMAs, so the address unit (16 clocks per dwordx4 instruction) never
-// backs up into the wave's in-order issue.  The branches are scalar and keep MFMAs and loads in
-// source order without further scheduling directives.
-template <bool SPLITW>
-__device__ __forceinline__ void pp_mfma_and_loads(const PpFrags& f, f32x16 (&acc)[4][2], bool load,
-                                                  __amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rw,
-                                                  __amdgpu_buffer_rsrc_t rw2, int kbyte,
-                                                  const uint32_t (&voff)[8], bf16* sA, bf16* sB, int w4) {
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j][kk], f.a[i][kk], acc[i][j], 0, 0, 0);
-      if (load) {
-        const int slot = kk * 4 + i;            // 0..15: slots 0..7 load A rows, 8..15 load W rows
-        const int base_row = (w4 * 8 + (slot & 7)) * 8;
-        if (slot < 8)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(
-              ra, (__attribute__((address_space(3))) void*)(sA + base_row * kBK), 16, voff[slot & 7], kbyte, 0, 0);
-        else
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(
-              (SPLITW && (slot & 7) >= 4) ? rw2 : rw, (__attribute__((address_space(3))) void*)(sB + base_row * kBK),
-              16, voff[SPLITW ? (slot & 3) : (slot & 7)], kbyte, 0, 0);
-      }
-    }
-}
-
-__device__ __forceinline__ void pp_barrier() {
+__device__ __forceinline__ void w4_barrier() {
   __builtin_amdgcn_sched_barrier(0);
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_sched_barrier(0);
@@ -272,10 +253,11 @@ __device__ __forceinline__ void pp_barrier() {
 
 // EPI selects the epilogue: bf16 store, fp32 residual read-modify-write, (split-K) fp32 partial
 // sums to a workspace [split][M][N] that splitk_reduce_kernel adds up in a fixed order, or the
-// fused SwiGLU: W is [2N][K] = [gate rows | up rows], the tile covers 128 FFN columns, each
-// wave's two 32-column accumulator blocks are gate and up of the same columns, and the output
-// [M][N] is silu(bf16(gate)) * bf16(up) -- the values, rounding included, that the separate
-// gate_up GEMM + silu_mul operators produce, without the [M][2N] round trip through HBM.
+// fused SwiGLU: W is [2N][K] = [gate rows | up rows], the tile covers 128 FFN columns, the 128 W
+// rows a wave multiplies are 64 gate rows followed by the 64 up rows of the same columns, so its
+// accumulator blocks [i][0..1] and [i][2..3] are gate and up of the same output elements, and the
+// output [M][N] is silu(bf16(gate)) * bf16(up) -- the values, rounding included, that the
+// separate gate_up GEMM + silu_mul operators produce, without the [M][2N] round trip through HBM.
 enum { kEpiBf16 = 0, kEpiResidual = 1, kEpiPartial = 2, kEpiSwiGLU = 3 };
 
 //
@@ -285,7 +267,7 @@ enum { kEpiBf16 = 0, kEpiResidual = 1, kEpiPartial = 2, kEpiSwiGLU = 3 };
 // matrix (W holds the experts' matrices back to back) into the same rows of C.  The grid is sized
 // for the worst case on the host; workgroups past groups[0] row tiles return at once.
 template <int EPI, bool GROUPED = false>
-__global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restrict__ A,
+__global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restrict__ A,
                                                            const bf16* __restrict__ W,
                                                            void* __restrict__ Cout, int M, int N,
                                                            int K, int tiles_m, int tiles_n,
@@ -298,13 +280,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
   __shared__ __attribute__((aligned(1024))) bf16 sA1[BM * kBK];
   __shared__ __attribute__((aligned(1024))) bf16 sB0[256 * kBK];
   __shared__ __attribute__((aligned(1024))) bf16 sB1[256 * kBK];
+  __shared__ __attribute__((aligned(256))) uint32_t sWarm[4 * 64];   // landing pad of the L2 warm-up loads
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int group = wave >> 2;
-  const int wm = wave & 1, wn = wave >> 1;           // 2 x 4 waves, wave tile 128 x 64
-  int tile_m, tile_n;
+  const int wm = wave & 1, wn = wave >> 1;           // 2 x 2 waves, wave tile 128 x 128 (SwiGLU: 128 x 64 outputs)
+  int tile_m, tile_n, share_m;
   const int n_tiles = tiles_m * tiles_n;
   const int split = GROUPED ? 0 : blockIdx.x / n_tiles;   // which K range (0 unless split-K)
   if (GROUPED) {
@@ -313,161 +295,147 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
     const int expert = groups[1 + 3 * ti], first = groups[2 + 3 * ti];
     M = groups[3 + 3 * ti];
     A += (int64_t)first * K;
-    W += (int64_t)expert * (EPI == kEpiSwiGLU ? 2 : 1) * N * K;
-    Cout = reinterpret_cast<char*>(Cout) + (int64_t)first * N * (EPI == kEpiBf16 || EPI == kEpiSwiGLU ? 2 : 4);
+    W += (int64_t)expert * (SWIGLU ? 2 : 1) * N * K;
+    Cout = reinterpret_cast<char*>(Cout) + (int64_t)first * N * (EPI == kEpiBf16 || SWIGLU ? 2 : 4);
     tile_m = 0;
     tile_n = blockIdx.x - ti * tiles_n;
+    share_m = ti;
   } else {
     tile_of_workgroup(blockIdx.x - split * n_tiles, tiles_m, tiles_n, tile_m, tile_n);
+    share_m = tile_m;
   }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int kt_first = split * kt_per_split;
   const int kt_count = min(kt_per_split, K / kBK - kt_first);
   const int kbyte0 = kt_first * kBK * 2;
 
-  // Per-lane byte offsets of the DMA sources inside the tile's row panel (the same for the A
-  // and the W panel: both have K as row stride).  The four waves of group 1 load whole k-tiles:
-  // wave w4 covers rows [64*w4, 64*w4+64) of each operand, 8 rows per instruction.
-  const int w4 = wave & 3;
+  // DMA sources.  Wave w fetches LDS rows [64w, 64w+64) of each operand, 8 rows per instruction;
+  // voff[j] is lane's byte offset inside the wave's 64-row panel for instruction j (the same for A
+  // and W: both have K as row stride): row 8j + lane/8, 16-byte chunk (lane%8) ^ swizzle key.
   uint32_t voff[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const int row = (w4 * 8 + j) * 8 + (lane >> 3);
+    const int row = j * 8 + (lane >> 3);
     const int ch = (lane & 7) ^ ((row >> 1) & 7);
     voff[j] = (uint32_t)((row * K + ch * 8) * 2);
   }
-  const __amdgpu_buffer_rsrc_t rsrc_a =
-      pp_panel_rsrc(A + (int64_t)m0 * K, (uint32_t)(min(BM, M - m0) * K * 2));
-  // SwiGLU: gate rows n0 + 32*w4 .. +31 and up rows N + n0 + 32*w4 .. +31 sit at LDS rows 64*w4 ..
-  // of the W stage; shifting each panel's base back by 32*w4 rows makes voff[0..3] (built for LDS
-  // rows 64*w4 + 0..31) address them, and the bound moves with it.
-  const int w_shift = SWIGLU ? 32 * w4 : 0;
-  const uint32_t w_bytes = (uint32_t)((w_shift + min(BN, N - n0)) * K * 2);
-  const __amdgpu_buffer_rsrc_t rsrc_w = pp_panel_rsrc(W + ((int64_t)n0 - w_shift) * K, w_bytes);
-  const __amdgpu_buffer_rsrc_t rsrc_w2 =
-      pp_panel_rsrc(W + ((int64_t)N + n0 - w_shift) * K, SWIGLU ? w_bytes : 0u);
+  // Plain: W rows n0 + 64w ..; SwiGLU: LDS rows 128*wn + (0..63) are gate rows n0 + 64*wn + (0..63),
+  // rows 128*wn + 64 + (0..63) the up rows N + the same -- waves 2*wn and 2*wn+1 fetch them.
+  const int w_col0 = SWIGLU ? n0 + 64 * (wave >> 1) : n0 + 64 * wave;
+  const int64_t w_row0 = SWIGLU ? (int64_t)(wave & 1) * N + w_col0 : w_col0;
+  const int a_rows = __builtin_amdgcn_readfirstlane(min(64, max(0, M - m0 - 64 * wave)));
+  const int w_rows = __builtin_amdgcn_readfirstlane(min(64, max(0, N - w_col0)));
+  const __amdgpu_buffer_rsrc_t rsrc_a = panel_rsrc(A + (int64_t)(m0 + 64 * wave) * K, (uint32_t)(a_rows * K * 2));
+  const __amdgpu_buffer_rsrc_t rsrc_w = panel_rsrc(W + w_row0 * K, (uint32_t)(w_rows * K * 2));
+  const __amdgpu_buffer_rsrc_t rsrc_none = panel_rsrc(A, 0u);
+  bf16* const dA0 = sA0 + 64 * wave * kBK;
+  bf16* const dA1 = sA1 + 64 * wave * kBK;
+  bf16* const dB0 = sB0 + 64 * wave * kBK;
+  bf16* const dB1 = sB1 + 64 * wave * kBK;
 
-  f32x16 acc[4][2];
+  // L2 warm-up sources: wave 0 lane l -> A row 4l + share, wave 1 lane l < 32 -> W-stage row 8l +
+  // share (SwiGLU: stage row r is gate row n0 + 64*(r/128) + r%64, or the up row N + that, for
+  // r%128 >= 64).  The share is added through the scalar offset.
+  uint32_t* const warm = sWarm + 64 * wave;
+  const int warm_rows_a = __builtin_amdgcn_readfirstlane(min(BM, M - m0));
+  const int warm_rows_w = __builtin_amdgcn_readfirstlane(SWIGLU ? N + min(BN, N - n0) : min(BN, N - n0));
+  const __amdgpu_buffer_rsrc_t rsrc_warm_a = panel_rsrc(A + (int64_t)m0 * K, (uint32_t)(warm_rows_a * K * 2));
+  const __amdgpu_buffer_rsrc_t rsrc_warm_w = panel_rsrc(W + (int64_t)n0 * K, (uint32_t)(warm_rows_w * K * 2));
+  const __amdgpu_buffer_rsrc_t rsrc_warm = wave == 0 ? rsrc_warm_a : wave == 1 ? rsrc_warm_w : rsrc_none;
+  const int warm_mask = wave == 0 ? 3 : 7;
+  const int warm_id = wave == 0 ? (tile_n & 3) : (share_m & 7);
+  uint32_t voff_warm;
+  {
+    const int r0 = lane * 8;                         // wave 1: W-stage row of this lane's share 0
+    const int64_t wrow = SWIGLU ? (int64_t)((r0 >> 6) & 1) * N + 64 * (r0 >> 7) + (r0 & 63) : r0;
+    voff_warm = wave == 0 ? (uint32_t)(lane * 4 * K * 2) : lane < 32 ? (uint32_t)(wrow * K * 2) : kOffOutOfRange;
+  }
+
+  f32x16 acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  if (group == 1) {
-    pp_issue_tile<SWIGLU>(rsrc_a, rsrc_w, rsrc_w2, kbyte0, voff, sA0, sB0, w4);
-    if (kt_count > 1) pp_issue_tile<SWIGLU>(rsrc_a, rsrc_w, rsrc_w2, kbyte0 + kBK * 2, voff, sA1, sB1, w4);
-    __builtin_amdgcn_s_waitcnt(kWaitVm0);
-  }
-  pp_barrier();
-
+  // MFMA fragment addresses: lane reads row (lane%32) of each 32-row block, k-chunk 2*kk + lane/32
+  // of k-step kk, at its swizzled position.
   const int frag_row = lane & 31, half = lane >> 5;
   const int key = (lane >> 1) & 7;
-  const int a_row0 = wm * 128 + frag_row, b_row0 = wn * 64 + frag_row;
-  PpFrags f;
+  int pch[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) pch[kk] = ((kk * 2 + half) ^ key) << 3;
+  const bf16* const rA0 = sA0 + (wm * 128 + frag_row) * kBK;
+  const bf16* const rA1 = sA1 + (wm * 128 + frag_row) * kBK;
+  const bf16* const rB0 = sB0 + (wn * 128 + frag_row) * kBK;
+  const bf16* const rB1 = sB1 + (wn * 128 + frag_row) * kBK;
 
-  // One iteration = memory phase + compute phase of k-tile t on the given stage.
-  auto iteration = [&](int t, bf16* sA, bf16* sB, bf16* sA_other, bf16* sB_other) {
-    // -- memory phase --
-    pp_read_frags(sA, sB, a_row0, b_row0, key, half, f);
-    if (group == 1) __builtin_amdgcn_s_waitcnt(kWaitVm0);   // k-tile t+1, issued one iteration ago
-    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
-    pp_barrier();
-    // -- compute phase --
-    // Both groups have finished reading this stage (group 0 one phase ago, group 1 just now):
-    // group 1 refills it with k-tile t+2 while it computes.
-    pp_mfma_and_loads<SWIGLU>(f, acc, group == 1 && t + 2 < kt_count, rsrc_a, rsrc_w, rsrc_w2,
-                              kbyte0 + (t + 2) * kBK * 2, voff, sA, sB, w4);
-    pp_barrier();
-  };
-
-  if (group == 1) pp_barrier();                          // run half an iteration behind group 0
-  for (int t = 0; t < kt_count; t += 2) {
-    iteration(t, sA0, sB0, sA1, sB1);
-    if (t + 1 < kt_count) iteration(t + 1, sA1, sB1, sA0, sB0);
+  // Prologue: k-tile 0 into stage 0 (awaited), the A rows of k-tile 1 into stage 1 (in flight).
+#pragma unroll
+  for (int s = 0; s < 8; ++s) w4_dma(rsrc_a, dA0 + s * 8 * kBK, voff[s], kbyte0);
+#pragma unroll
+  for (int s = 0; s < 8; ++s) w4_dma(rsrc_w, dB0 + s * 8 * kBK, voff[s], kbyte0);
+  {
+    const __amdgpu_buffer_rsrc_t ra1 = kt_count > 1 ? rsrc_a : rsrc_none;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) w4_dma(ra1, dA1 + s * 8 * kBK, voff[s], kbyte0 + kBK * 2);
   }
-  if (group == 0) pp_barrier();
+  __builtin_amdgcn_s_waitcnt(kWaitVm8);
+  w4_barrier();
+  W4Frags f0, f1;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    f0.a[s] = *reinterpret_cast<const bf16x8*>(rA0 + s * 32 * kBK + pch[0]);
+    f0.b[s] = *reinterpret_cast<const bf16x8*>(rB0 + s * 32 * kBK + pch[0]);
+  }
+  __builtin_amdgcn_sched_barrier(0);
 
-  // Epilogue.  The MFMAs take the W fragment as their row operand, so each 32x32 accumulator is
-  // a block of C^T: lane l holds output row m = l%32 and, per register quad a, the four
-  // consecutive columns n = 8a + 4*(l/32) + (0..3).
-  // Each wave stages its block through its own 16 KB of the (now idle) LDS stages so that global
-  // memory sees whole 128-byte row segments (8 full cache lines per instruction) instead of the
-  // 8/16-byte pieces the accumulator layout would give.
-  bf16* region = (wave >> 1) == 0 ? sA0 : (wave >> 1) == 1 ? sA1 : (wave >> 1) == 2 ? sB0 : sB1;
-  region += (wave & 1) * (128 * 64);
+  // k-tile t on stage c (the other stage: o).  On entry f0 holds k-step 0 of tile t and the A rows
+  // of tile t+1 are in flight to stage o.  k-step 0 adds the W rows of tile t+1 and the warm-up
+  // load for tile t+3; after k-step 2 everything but that load must have landed; the barrier tells
+  // all waves that tile t+1 is complete and stage c is free; k-step 3 (fed from registers) refills
+  // stage c with the A rows of tile t+2 and starts reading tile t+1.
+#define W4_TILE(t, c, o)                                                                                      \
+  {                                                                                                           \
+    const int t1_ = (t) + 1, t2_ = (t) + 2, tw_ = (t) + kWarmAhead;                                           \
+    w4_block<true>(acc, f0, f1, rA##c, rB##c, pch[1], t1_ < kt_count ? rsrc_w : rsrc_none, dB##o, voff,       \
+                   kbyte0 + t1_ * kBK * 2);                                                                   \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(tw_ < kt_count ? rsrc_warm : rsrc_none,                          \
+                                             (__attribute__((address_space(3))) void*)warm, 4, voff_warm,     \
+                                             kbyte0 + tw_ * kBK * 2 + ((warm_id - tw_) & warm_mask) * K * 2, 0, 0); \
+    __builtin_amdgcn_sched_barrier(0);                                                                        \
+    w4_block<false>(acc, f1, f0, rA##c, rB##c, pch[2], rsrc_none, dB##o, voff, 0);                            \
+    w4_block<false>(acc, f0, f1, rA##c, rB##c, pch[3], rsrc_none, dB##o, voff, 0);                            \
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);                                                                   \
+    __builtin_amdgcn_s_waitcnt(kWaitVm1);                                                                     \
+    w4_barrier();                                                                                             \
+    w4_block<true>(acc, f1, f0, rA##o, rB##o, pch[0], t2_ < kt_count ? rsrc_a : rsrc_none, dA##c, voff,       \
+                   kbyte0 + t2_ * kBK * 2);                                                                   \
+  }
+  int t = 0;
+  for (; t + 1 < kt_count; t += 2) {
+    W4_TILE(t, 0, 1);
+    W4_TILE(t + 1, 1, 0);
+  }
+  if (t < kt_count) W4_TILE(t, 0, 1);
+#undef W4_TILE
+  __builtin_amdgcn_s_waitcnt(kWaitVm0);      // the trailing (empty) DMA writes have landed
+  __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+  w4_barrier();                              // before the stages are reused for the epilogue
+
+  // Epilogue.  The MFMAs take the W fragment as their row operand, so each 32x32 accumulator is a
+  // block of C^T: lane l holds output row m = l%32 and, per register quad a, the four consecutive
+  // columns n = 8a + 4*(l/32) + (0..3).  The wave stages its block through its own 32 KB of the
+  // (now idle) LDS stages so that global memory sees whole row segments of 128-256 bytes.  Global
+  // accesses go through a buffer descriptor over the wave's valid rows (rows past M fall outside
+  // it, columns past N get an out-of-range offset): no branches, so the stores -- and the residual
+  // reads, 16 row segments at a time -- are in flight together instead of one after the other.
+  bf16* region = wave == 0 ? sA0 : wave == 1 ? sA1 : wave == 2 ? sB0 : sB1;
+  const int rows_valid = __builtin_amdgcn_readfirstlane(min(128, max(0, M - m0 - wm * 128)));
   if (SWIGLU) {
-    // acc[i][0] = gate, acc[i][1] = up for output columns n0 + 32*wn + (0..31).  Staged as
-    // [128 rows][4 chunks of 8 bf16], chunk c of row r at position c ^ ((r>>2)&3), then stored as
-    // 64-byte row segments with 16-byte accesses.
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = i * 32 + frag_row;
-      const int rkey = (row >> 2) & 3;
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        bf16x4 v;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const float g = static_cast<float>(static_cast<bf16>(acc[i][0][4 * a + b]));
-          const float u = static_cast<float>(static_cast<bf16>(acc[i][1][4 * a + b]));
-          v[b] = static_cast<bf16>(silu_mul_f32(g, u));
-        }
-        *reinterpret_cast<bf16x4*>(region + row * 32 + ((a ^ rkey) << 3) + 4 * half) = v;
-      }
-    }
-    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);     // own wave's LDS writes have landed; no other wave touches the region
-    bf16* cbase = reinterpret_cast<bf16*>(Cout) + (int64_t)(m0 + wm * 128) * N + n0 + wn * 32;
-#pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int idx = lane + it * 64;
-      const int row = idx >> 2, ch = idx & 3;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(region + row * 32 + ((ch ^ ((row >> 2) & 3)) << 3));
-      if (m0 + wm * 128 + row < M && n0 + wn * 32 + ch * 8 < N)
-        *reinterpret_cast<u32x4*>(cbase + (int64_t)row * N + ch * 8) = v;
-    }
-  } else if (EPI != kEpiBf16) {
-    // fp32 residual (read-modify-write) or split-K partial (plain store into this split's
-    // [M][N] slab): two passes of 32 columns, staged as [128 rows][8 chunks of 4 floats], chunk c
-    // of row r at position c ^ ((r>>1)&7).
-    float* stage = reinterpret_cast<float*>(region);
-    float* cf = reinterpret_cast<float*>(Cout) + (EPI == kEpiPartial ? (int64_t)split * M * N : 0) +
-                (int64_t)(m0 + wm * 128) * N + n0 + wn * 64;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = i * 32 + frag_row;
-        const int rkey = (row >> 1) & 7;
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          f32x4 v;
-#pragma unroll
-          for (int b = 0; b < 4; ++b) v[b] = acc[i][j][4 * a + b];
-          *reinterpret_cast<f32x4*>(stage + row * 32 + (((2 * a + half) ^ rkey) << 2)) = v;
-        }
-      }
-      __builtin_amdgcn_s_waitcnt(kWaitLgkm0);   // own wave's LDS writes have landed; no other wave touches the region
-#pragma unroll
-      for (int it = 0; it < 16; ++it) {
-        const int idx = lane + it * 64;
-        const int row = idx >> 3, ch = idx & 7;
-        f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * 32 + ((ch ^ ((row >> 1) & 7)) << 2));
-        if (m0 + wm * 128 + row < M && n0 + wn * 64 + j * 32 + ch * 4 < N) {   // N % 8 == 0: quads all-in or all-out
-          f32x4* c = reinterpret_cast<f32x4*>(cf + (int64_t)row * N + j * 32 + ch * 4);
-          if (RESID) {
-            const f32x4 x = *c;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) v[b] += x[b];
-          }
-          *c = v;
-        }
-      }
-    }
-  } else {
-    // bf16 output: staged as [128 rows][8 chunks of 8 bf16], chunk c of row r at position
-    // c ^ ((r>>1)&7), then stored as whole 128-byte rows with 16-byte accesses.
+    // Outputs n0 + 64*wn + (0..63): staged as [128 rows][8 chunks of 8 bf16], chunk c of row r at
+    // position c ^ ((r>>1)&7).
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = i * 32 + frag_row;
@@ -478,19 +446,108 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(const bf16* __restric
         for (int a = 0; a < 4; ++a) {
           bf16x4 v;
 #pragma unroll
-          for (int b = 0; b < 4; ++b) v[b] = static_cast<bf16>(acc[i][j][4 * a + b]);
+          for (int b = 0; b < 4; ++b) {
+            const float g = static_cast<float>(static_cast<bf16>(acc[i][j][4 * a + b]));
+            const float u = static_cast<float>(static_cast<bf16>(acc[i][2 + j][4 * a + b]));
+            v[b] = static_cast<bf16>(silu_mul_f32(g, u));
+          }
           *reinterpret_cast<bf16x4*>(region + row * 64 + (((j * 4 + a) ^ rkey) << 3) + 4 * half) = v;
         }
     }
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);     // own wave's LDS writes have landed; no other wave touches the region
-    bf16* cbase = reinterpret_cast<bf16*>(Cout) + (int64_t)(m0 + wm * 128) * N + n0 + wn * 64;
+    bf16* cb = reinterpret_cast<bf16*>(Cout) + (int64_t)(m0 + wm * 128) * N;
+    const __amdgpu_buffer_rsrc_t rc = panel_rsrc(cb, (uint32_t)(rows_valid * N * 2));
+    const int col = n0 + wn * 64 + (lane & 7) * 8;
+    const uint32_t cbyte = col < N ? (uint32_t)(((lane >> 3) * N + col) * 2) : kOffOutOfRange;
 #pragma unroll
     for (int it = 0; it < 16; ++it) {
       const int idx = lane + it * 64;
       const int row = idx >> 3, ch = idx & 7;
       const u32x4 v = *reinterpret_cast<const u32x4*>(region + row * 64 + ((ch ^ ((row >> 1) & 7)) << 3));
-      if (m0 + wm * 128 + row < M && n0 + wn * 64 + ch * 8 < N)
-        *reinterpret_cast<u32x4*>(cbase + (int64_t)row * N + ch * 8) = v;
+      __builtin_amdgcn_raw_buffer_store_b128(v, rc, cbyte, it * 8 * N * 2, 0);
+    }
+  } else if (EPI == kEpiBf16) {
+    // [128 rows][16 chunks of 8 bf16], chunk c of row r at position c ^ (r & 15).
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = i * 32 + frag_row;
+      const int rkey = row & 15;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          bf16x4 v;
+#pragma unroll
+          for (int b = 0; b < 4; ++b) v[b] = static_cast<bf16>(acc[i][j][4 * a + b]);
+          *reinterpret_cast<bf16x4*>(region + row * 128 + (((j * 4 + a) ^ rkey) << 3) + 4 * half) = v;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    bf16* cb = reinterpret_cast<bf16*>(Cout) + (int64_t)(m0 + wm * 128) * N;
+    const __amdgpu_buffer_rsrc_t rc = panel_rsrc(cb, (uint32_t)(rows_valid * N * 2));
+    const int col = n0 + wn * 128 + (lane & 15) * 8;
+    const uint32_t cbyte = col < N ? (uint32_t)(((lane >> 4) * N + col) * 2) : kOffOutOfRange;
+#pragma unroll
+    for (int it = 0; it < 32; ++it) {
+      const int idx = lane + it * 64;
+      const int row = idx >> 4, ch = idx & 15;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(region + row * 128 + ((ch ^ (row & 15)) << 3));
+      __builtin_amdgcn_raw_buffer_store_b128(v, rc, cbyte, it * 4 * N * 2, 0);
+    }
+  } else {
+    // fp32 residual (read-modify-write) or split-K partial (plain store into this split's [M][N]
+    // slab): two passes of 64 columns, staged as [128 rows][16 chunks of 4 floats], chunk c of row r
+    // at position c ^ (r & 15).
+    float* stage = reinterpret_cast<float*>(region);
+    float* cf = reinterpret_cast<float*>(Cout) + (EPI == kEpiPartial ? (int64_t)split * M * N : 0) +
+                (int64_t)(m0 + wm * 128) * N;
+    const __amdgpu_buffer_rsrc_t rc = panel_rsrc(cf, (uint32_t)(rows_valid * N * 4));
+    const int col0 = n0 + wn * 128 + (lane & 15) * 4;
+#pragma unroll
+    for (int jp = 0; jp < 2; ++jp) {
+      const int col = col0 + jp * 64;
+      const uint32_t cbyte = col < N ? (uint32_t)(((lane >> 4) * N + col) * 4) : kOffOutOfRange;   // N % 8 == 0: quads all-in or all-out
+      f32x4 x[16];
+      if (RESID) {
+#pragma unroll
+        for (int it = 0; it < 16; ++it)
+          x[it] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rc, cbyte, it * 4 * N * 4, 0));
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = i * 32 + frag_row;
+        const int rkey = row & 15;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int a = 0; a < 4; ++a) {
+            f32x4 v;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) v[b] = acc[i][jp * 2 + jj][4 * a + b];
+            *reinterpret_cast<f32x4*>(stage + row * 64 + (((jj * 8 + 2 * a + half) ^ rkey) << 2)) = v;
+          }
+      }
+      __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        if (RESID && h == 1) {
+#pragma unroll
+          for (int it = 0; it < 16; ++it)
+            x[it] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rc, cbyte, (16 + it) * 4 * N * 4, 0));
+        }
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+          const int idx = lane + (h * 16 + it) * 64;
+          const int row = idx >> 4, ch = idx & 15;
+          f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * 64 + ((ch ^ (row & 15)) << 2));
+          if (RESID) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) v[b] += x[it][b];
+          }
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rc, cbyte, (h * 16 + it) * 4 * N * 4, 0);
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(kWaitLgkm0);   // the stage is rewritten by the next pass
     }
   }
 }
@@ -523,7 +580,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // How many K ranges to cut a problem into so that a launch has about one workgroup per CU:
 // only when the 256x256 tiles alone leave most of the chip idle, and never below 8 k-tiles
 // (512 columns) per range.  1 = no split.
-static int pp_splits(int64_t m, int64_t n, int64_t k) {
+static int w4_splits(int64_t m, int64_t n, int64_t k) {
   const int64_t tiles = ((m + 255) / 256) * ((n + 255) / 256);
   if (tiles <= 0 || tiles >= 160) return 1;
   int s = (int)std::min<int64_t>(16, 256 / tiles);
@@ -534,13 +591,13 @@ static int pp_splits(int64_t m, int64_t n, int64_t k) {
 bool gemm_swiglu_fusable(int dtype, int64_t m, int64_t f, int64_t k) {
   if (dtype != 1 || k % kBK != 0 || f % 8 != 0 || m <= 0) return false;
   const int64_t tiles = ((m + 255) / 256) * ((f + 127) / 128);
-  return tiles >= 96 && pp_splits(m, 2 * f, k) == 1;
+  return tiles >= 96 && w4_splits(m, 2 * f, k) == 1;
 }
 
 void launch_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t m, int64_t f,
                         int64_t k, hipStream_t s) {
   const int tiles_m = (int)((m + 255) / 256), tiles_n = (int)((f + 127) / 128);
-  gemm_bf16_pp_kernel<kEpiSwiGLU><<<dim3((unsigned)(tiles_m * tiles_n)), 512, 0, s>>>(
+  gemm_bf16_w4_kernel<kEpiSwiGLU><<<dim3((unsigned)(tiles_m * tiles_n)), 256, 0, s>>>(
       (const bf16*)a, (const bf16*)w_gate_up, out, (int)m, (int)f, (int)k, tiles_m, tiles_n,
       (int)(k / kBK), nullptr);
 }
@@ -550,32 +607,32 @@ void launch_gemm_grouped(const void* a, const void* w, void* c, int64_t n, int64
   const int tiles_n = (int)(swiglu ? (n + 127) / 128 : (n + 255) / 256);
   const dim3 grid((unsigned)(max_row_tiles * tiles_n));
   if (swiglu)
-    gemm_bf16_pp_kernel<kEpiSwiGLU, true><<<grid, 512, 0, s>>>((const bf16*)a, (const bf16*)w, c, 0, (int)n,
+    gemm_bf16_w4_kernel<kEpiSwiGLU, true><<<grid, 256, 0, s>>>((const bf16*)a, (const bf16*)w, c, 0, (int)n,
                                                               (int)k, max_row_tiles, tiles_n, (int)(k / kBK), groups);
   else
-    gemm_bf16_pp_kernel<kEpiBf16, true><<<grid, 512, 0, s>>>((const bf16*)a, (const bf16*)w, c, 0, (int)n,
+    gemm_bf16_w4_kernel<kEpiBf16, true><<<grid, 256, 0, s>>>((const bf16*)a, (const bf16*)w, c, 0, (int)n,
                                                             (int)k, max_row_tiles, tiles_n, (int)(k / kBK), groups);
 }
 
 size_t gemm_workspace_bytes(int dtype, int64_t m, int64_t n, int64_t k) {
   if (dtype != 1 || k % kBK != 0) return 0;
-  const int s = pp_splits(m, n, k);
+  const int s = w4_splits(m, n, k);
   return s > 1 ? (size_t)s * m * n * sizeof(float) : 0;
 }
 
 template <bool RESID>
-static void launch_bf16_pp(const bf16* a, const bf16* w, void* c, int m, int n, int k, int splits,
+static void launch_bf16_w4(const bf16* a, const bf16* w, void* c, int m, int n, int k, int splits,
                            float* workspace, hipStream_t s) {
   const int tiles_m = (m + 255) / 256, tiles_n = (n + 255) / 256;
   const int kt = k / kBK;
   if (splits <= 1) {
-    gemm_bf16_pp_kernel<RESID ? kEpiResidual : kEpiBf16>
-        <<<dim3((unsigned)(tiles_m * tiles_n)), 512, 0, s>>>(a, w, c, m, n, k, tiles_m, tiles_n, kt, nullptr);
+    gemm_bf16_w4_kernel<RESID ? kEpiResidual : kEpiBf16>
+        <<<dim3((unsigned)(tiles_m * tiles_n)), 256, 0, s>>>(a, w, c, m, n, k, tiles_m, tiles_n, kt, nullptr);
     return;
   }
   const int per = (kt + splits - 1) / splits;
   const int used = (kt + per - 1) / per;             // every launched split has at least one k-tile
-  gemm_bf16_pp_kernel<kEpiPartial><<<dim3((unsigned)(tiles_m * tiles_n * used)), 512, 0, s>>>(
+  gemm_bf16_w4_kernel<kEpiPartial><<<dim3((unsigned)(tiles_m * tiles_n * used)), 256, 0, s>>>(
       a, w, workspace, m, n, k, tiles_m, tiles_n, per, nullptr);
   const int64_t mn = (int64_t)m * n;
   splitk_reduce_kernel<RESID><<<dim3((unsigned)((mn / 8 + 255) / 256)), 256, 0, s>>>(workspace, c, mn / 8,
@@ -663,14 +720,14 @@ void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, in
   const bf16* pa = (const bf16*)a;
   const bf16* pw = (const bf16*)w;
   // K a multiple of 64 and enough 256x256 tiles (or enough K to split) to occupy the chip: the
-  // ping-pong DMA kernel, split over K when the caller's workspace allows.  Otherwise (tiny or
+  // one-wave-per-SIMD DMA kernel, split over K when the caller's workspace allows.  Otherwise (tiny or
   // odd-K problems): the register-staged kernel on 128x128 tiles.
   const int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
-  int splits = k % kBK == 0 ? pp_splits(m, n, k) : 1;
+  int splits = k % kBK == 0 ? w4_splits(m, n, k) : 1;
   if (splits > 1 && (size_t)splits * m * n * sizeof(float) > workspace_bytes) splits = 1;
-  if (k % kBK == 0 && big_tiles * splits >= 96) {
-    if (residual) launch_bf16_pp<true>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, s);
-    else launch_bf16_pp<false>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, s);
+  if (k % kBK == 0 && n % 8 == 0 && big_tiles * splits >= 96) {
+    if (residual) launch_bf16_w4<true>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, s);
+    else launch_bf16_w4<false>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, s);
   } else {
     if (residual) launch_bf16_cfg<128, 128, 2, 2, true>(pa, pw, c, (int)m, (int)n, (int)k, s);
     else launch_bf16_cfg<128, 128, 2, 2, false>(pa, pw, c, (int)m, (int)n, (int)k, s);
