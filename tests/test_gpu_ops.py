@@ -53,6 +53,35 @@ def test_gemm_residual_accumulates_into_fp32(name, m, n, k):
     assert max_rel_err(x, ref) <= TOL[name]
 
 
+@pytest.mark.parametrize("residual", [False, True])
+@pytest.mark.parametrize("m,n,k", [
+    (2304, 2816, 64), (2304, 2816, 128), (2304, 2816, 192), (2560, 2560, 448), (2560, 2560, 576),
+    (2560, 2560, 1088), (2561, 2568, 704), (2049, 3080, 1600),
+])
+def test_gemm_fast_path_trip_counts_and_ragged_edges(residual, m, n, k):
+    """The 256x256-tile MFMA kernel on every path of its K loop (1, 2, 3, 7, 9, 11, 17 and 25
+    k-tiles: single tiles, pairs, the eight-tile trip and their mixes), with a last row tile of
+    one row and a last column tile of eight columns; rows behind the output must stay untouched."""
+    B = _binding()
+    print(f"gemm fast path residual={residual} m={m} n={n} k={k}", flush=True)
+    a = I.normal_tensor((m, k), 1.0, 21, torch.bfloat16, "cuda")
+    w = I.normal_tensor((n, k), 0.05, 22, torch.bfloat16, "cuda")
+    td = torch.float32 if residual else torch.bfloat16
+    guard = 300
+    buf = torch.full((m + guard, n), 7.0, dtype=td, device="cuda")
+    if residual:
+        buf[:m] = I.normal_tensor((m, n), 1.0, 23, torch.float32, "cuda")
+    x0 = buf[:m].clone()
+    torch.cuda.synchronize()
+    B.fp_op_gemm(1, a.data_ptr(), w.data_ptr(), buf.data_ptr(), m, n, k, residual)
+    torch.cuda.synchronize()
+    ref = O.linear(a.cpu(), w.cpu())
+    if residual:
+        ref = ref + x0.cpu().double()
+    assert max_rel_err(buf[:m], ref) <= TOL["bf16"]
+    assert torch.all(buf[m:] == 7.0)
+
+
 @pytest.mark.parametrize("name", ["bf16", "fp32"])
 @pytest.mark.parametrize("t,d", [(1, 256), (77, 4096), (5, 5120), (3, 8200), (2, 20000)])
 def test_rmsnorm_matches_definition(name, t, d):
@@ -82,7 +111,8 @@ def test_silu_mul_matches_definition(name, t, f):
     assert max_rel_err(out, ref) <= TOL[name]
 
 
-@pytest.mark.parametrize("m,f,k", [(8192, 14336, 4096), (1000, 14336, 4096), (3000, 1000, 256), (700, 27648, 5120)])
+@pytest.mark.parametrize("m,f,k", [(8192, 14336, 4096), (1000, 14336, 4096), (3000, 1000, 256), (700, 27648, 5120),
+                                   (2304, 1536, 64), (2305, 1544, 576)])
 def test_fused_gate_up_swiglu_equals_the_two_operators(m, f, k):
     """The gate_up GEMM with SiLU(gate)*up in its epilogue gives the bits of the GEMM followed by
     the stand-alone silu_mul (ragged M, an FFN width that is not a multiple of the 128-column
