@@ -23,7 +23,9 @@ constexpr int kOpsPerLayer = 9;
 // fp32 registers.  bf16: one 16-byte access; fp32: two 16-byte accesses.
 // SiLU(gate) * up in fp32: the one formula both the stand-alone operator and the fused GEMM
 // epilogue use, so the two give the same bits.
-__device__ __forceinline__ float silu_mul_f32(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+__device__ __forceinline__ float silu_mul_f32(float g, float u) {
+  return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;   // v_rcp_f32 (1 ulp) instead of the IEEE division sequence
+}
 
 template <typename T> struct Vec8;
 
