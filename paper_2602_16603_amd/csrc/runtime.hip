@@ -111,9 +111,11 @@ struct fp_prefill {
   TaskState state = TaskState::Idle;
   std::atomic<int> signal{0};
   hipEvent_t ring[kEventRing] = {};
+  hipEvent_t done_ev[kEventRing] = {};   // event that marks the completion of the k-th last operator (not owned)
   // per-op timing
   bool timing = false;
-  std::vector<hipEvent_t> tev;
+  std::vector<hipEvent_t> tev;          // recorded events, in order
+  std::vector<int32_t> tmark;           // tmark[i] = index in tev of the boundary before operator i of this call
   int32_t timed_ops = 0;
 };
 
@@ -569,7 +571,8 @@ fp_status fp_prefill_advance(fp_prefill* t, int32_t max_ops, int32_t* ops_done) 
     // Bound how far the host runs ahead of the device: operator i is launched only once
     // operator i - launch_ahead has completed.
     if (t->launch_ahead > 0 && issued >= t->launch_ahead) {
-      hipError_t e = hipEventSynchronize(t->ring[(issued - t->launch_ahead) % kEventRing]);
+      hipEvent_t ev = t->done_ev[(issued - t->launch_ahead) % kEventRing];
+      hipError_t e = ev ? hipEventSynchronize(ev) : hipSuccess;
       if (e != hipSuccess) { result = fail(FP_ERR_DEVICE, "event wait: %s", hipGetErrorString(e)); break; }
     }
     // Preemption check at the boundary after the previous operator (Section 5.1).
@@ -582,18 +585,37 @@ fp_status fp_prefill_advance(fp_prefill* t, int32_t max_ops, int32_t* ops_done) 
       finish(TaskState::Parked, true);
       return FP_PREEMPTED;
     }
-    if (t->timing) {
-      if ((int32_t)t->tev.size() < issued + 2) {
-        t->tev.resize((size_t)issued + 2, nullptr);
-      }
-      if (!t->tev[issued]) (void)hipEventCreate(&t->tev[issued]);
-      if (!t->tev[issued + 1]) (void)hipEventCreate(&t->tev[issued + 1]);
-      if (issued == 0) (void)hipEventRecord(t->tev[0], s);
+    // One event per operator serves both the launch-ahead bound and the timing read-out (an event
+    // record costs the device a few microseconds between two kernels); an operator that launches
+    // nothing (SiLU*up after the fused gate_up GEMM) records none and completes with its
+    // predecessor.
+    auto timing_event = [&]() -> hipEvent_t {
+      hipEvent_t ev = nullptr;
+      if (hipEventCreate(&ev) != hipSuccess) return nullptr;
+      t->tev.push_back(ev);
+      (void)hipEventRecord(ev, s);
+      return ev;
+    };
+    if (t->timing && issued == 0) {
+      for (auto& ev : t->tev) if (ev) (void)hipEventDestroy(ev);
+      t->tev.clear();
+      t->tmark.assign(1, 0);
+      (void)timing_event();
     }
+    const bool launches = !(t->swiglu_fused && t->cursor % FP_OPS_PER_LAYER == 7);
     fp_status st = launch_op(t, t->cursor);
     if (st != FP_OK) { result = st; break; }
-    if (t->timing) { (void)hipEventRecord(t->tev[issued + 1], s); t->timed_ops = issued + 1; }
-    if (t->launch_ahead > 0) (void)hipEventRecord(t->ring[issued % kEventRing], s);
+    hipEvent_t done = issued > 0 ? t->done_ev[(issued - 1) % kEventRing] : nullptr;
+    if (launches) {
+      if (t->timing) {
+        done = timing_event();
+      } else if (t->launch_ahead > 0) {
+        done = t->ring[issued % kEventRing];
+        (void)hipEventRecord(done, s);
+      }
+    }
+    if (t->timing) { t->tmark.push_back((int32_t)t->tev.size() - 1); t->timed_ops = issued + 1; }
+    t->done_ev[issued % kEventRing] = done;
     t->cursor++;
     issued++;
   }
@@ -700,8 +722,10 @@ fp_status fp_prefill_op_times(fp_prefill* t, float* ms_out, int32_t n, int32_t* 
   const int32_t cnt = std::min(n, t->timed_ops);
   for (int32_t i = 0; i < cnt; ++i) {
     float ms = 0.f;
-    hipError_t e = hipEventElapsedTime(&ms, t->tev[i], t->tev[i + 1]);
-    if (e != hipSuccess) return fail(FP_ERR_DEVICE, "elapsed time: %s", hipGetErrorString(e));
+    if (t->tmark[i] != t->tmark[i + 1]) {   // equal marks: the operator launched nothing
+      hipError_t e = hipEventElapsedTime(&ms, t->tev[t->tmark[i]], t->tev[t->tmark[i + 1]]);
+      if (e != hipSuccess) return fail(FP_ERR_DEVICE, "elapsed time: %s", hipGetErrorString(e));
+    }
     ms_out[i] = ms;
   }
   *n_out = cnt;
