@@ -610,6 +610,7 @@ static int w4_splits(int64_t m, int64_t n, int64_t k) {
 
 bool gemm_swiglu_fusable(int dtype, int64_t m, int64_t f, int64_t k) {
   if (dtype != 1 || k % kBK != 0 || f % 8 != 0 || m <= 0) return false;
+  if ((f + 256) * k * 2 >= (int64_t)kOffOutOfRange) return false;   // the kernel's 32-bit offsets into the [gate | up] panel
   const int64_t tiles = ((m + 255) / 256) * ((f + 127) / 128);
   return tiles >= 96 && w4_splits(m, 2 * f, k) == 1;
 }
