@@ -746,7 +746,8 @@ void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, in
   const int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
   int splits = k % kBK == 0 ? w4_splits(m, n, k) : 1;
   if (splits > 1 && (size_t)splits * m * n * sizeof(float) > workspace_bytes) splits = 1;
-  if (k % kBK == 0 && n % 8 == 0 && big_tiles * splits >= 96) {
+  // (the size limits keep the fast kernel's 32-bit buffer offsets below kOffOutOfRange)
+  if (k % kBK == 0 && n % 8 == 0 && n <= (1 << 21) && k <= (1 << 21) && big_tiles * splits >= 96) {
     if (residual) launch_bf16_w4<true>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, s);
     else launch_bf16_w4<false>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, s);
   } else {
