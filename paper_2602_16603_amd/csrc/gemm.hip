@@ -168,14 +168,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16* _
 // bf16 MFMA GEMM, one wave per SIMD (the fast path; K % 64 == 0).
 //
 // 256x256 output tile, K consumed 64 at a time, 256 threads = 4 waves, one per SIMD, each with the
-// whole 512-register budget: a wave owns a 128x128 block of the tile, 4x4 accumulators of 32x32 =
-// 256 accumulator registers.  The wave's instruction stream is software-pipelined by k-step (16 of
-// K = 16 MFMAs = 512 matrix-pipe cycles): between the MFMAs of one k-step sit the 8 LDS fragment
-// reads of the next one and the wave's share of the global loads, one of each per two MFMAs, so
-// the matrix pipe always has its next instruction queued; one s_barrier per k-tile.  The loop
-// body is straight-line code on purpose: the compiler keeps the 256 accumulators in place in the
-// accumulation registers only while no control flow crosses them, so "nothing left to fetch" is
-// expressed through an empty buffer descriptor, never through a branch.
+// whole 512-register budget: a wave owns a 128x128 block of the tile, 8x8 accumulators of 16x16 =
+// 256 accumulator registers, multiplied with v_mfma_f32_16x16x32_bf16 (on random operands the
+// register-only loop of this instruction sustains 2.0-2.1 PFLOP/s where 32x32x16 sustains
+// 1.8-1.9: the chip is power limited and the smaller accumulator costs less energy per FLOP).
+// The wave's instruction stream is software-pipelined by k-step (32 of K = 64 MFMAs = 1024
+// matrix-pipe cycles): every LDS fragment read of the next k-step and every global load sits
+// alone behind an MFMA, inside the 16 cycles the matrix pipe is busy with it; one s_barrier per
+// k-tile.  The loop body is straight-line code on purpose: the compiler keeps the 256
+// accumulators in place in the accumulation registers only while no control flow crosses them, so
+// "nothing left to fetch" is expressed through an empty buffer descriptor, never through a branch.
 //
 // Global -> LDS goes through the DMA path (buffer_load_dwordx4 ... lds: no VGPR staging, no
 // ds_write).  A DMA instruction writes lane i's 16 bytes at base + 16*i, i.e. one wave fills
@@ -183,9 +185,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16* _
 // global chunk each lane fetches.  Two LDS stages (A and W, 32 KB each per stage) as four
 // separate __shared__ arrays, so that the compiler can tell that DMA in flight to one stage does
 // not alias LDS reads of the other (otherwise it would serialise them with vmcnt(0)).  Wave w
-// fetches rows [64w, 64w+64) of both operands, 16 instructions per k-tile: the A rows in the
-// k-step after the barrier that frees the stage, the W rows in the next one; the remaining two
-// k-steps give them time to land.  Operand panels are addressed through raw buffer descriptors
+// fetches rows [64w, 64w+64) of both operands, 16 instructions per k-tile, all in the k-step after
+// the barrier that frees the stage; the other k-step gives them time to land.  Operand panels are addressed through raw buffer descriptors
 // sized to the valid rows, so row tails of A and W read as zero.
 //
 // L2 warm-up.  The 32 workgroups running on one XCD share operand panels (8 tile rows x 4 tile
@@ -201,14 +202,15 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16* _
 // ------------------------------------------------------------------------------------------
 constexpr int kWaitVm0 = 0x0F70;   // s_waitcnt vmcnt(0)           (expcnt/lgkmcnt untouched)
 constexpr int kWaitVm1 = 0x0F71;   // s_waitcnt vmcnt(1)
-constexpr int kWaitVm8 = 0x0F78;   // s_waitcnt vmcnt(8)
+constexpr int kWaitVm17 = 0x4F71;  // s_waitcnt vmcnt(17)
 constexpr int kWaitLgkm0 = 0xC07F; // s_waitcnt lgkmcnt(0)         (vmcnt/expcnt untouched)
 constexpr int kWarmAhead = 3;      // k-tiles between the L2 warm-up load and the DMA of the same lines
 constexpr uint32_t kOffOutOfRange = 0x80000000u;   // a byte offset no descriptor here covers
 
-struct W4Frags {     // MFMA operands of one k-step: four 32-row blocks of A and of W
-  bf16x8 a[4];
-  bf16x8 b[4];
+typedef float f32x4_acc __attribute__((ext_vector_type(4)));
+struct W4Frags {     // MFMA operands of one k-step (32 of K): eight 16-row blocks of A and of W
+  bf16x8 a[8];
+  bf16x8 b[8];
 };
 
 // Raw buffer descriptor over `bytes` bytes at `base` (stride 0, 32-bit offsets, reads past the
@@ -222,34 +224,41 @@ __device__ __forceinline__ void w4_dma(__amdgpu_buffer_rsrc_t r, bf16* lds_rows,
   __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)lds_rows, 16, voff, kbyte, 0, 0);
 }
 
-// One k-step: 16 MFMAs from `cur`; after every pair of them one fragment read of the next k-step
-// into `nxt` (in the order the next k-step first uses them: b0 b1 a0 b2 b3 a1 a2 a3) and, if DMA,
-// one of the wave's 8 DMA instructions for one operand (8 rows of 128 bytes each).  EARLY (the
-// k-step that ends at the barrier): two reads per pair, all issued in the first half, so that the
-// wait for them in front of the barrier finds them done.
-template <bool DMA, bool EARLY = false>
-__device__ __forceinline__ void w4_block(f32x16 (&acc)[4][4], const W4Frags& cur, W4Frags& nxt,
+// One k-step: 64 MFMAs from `cur` (A block s against the eight W blocks, s = 0..7).  Every other
+// instruction sits alone behind an MFMA: READS fragment reads of the next k-step per A block (2:
+// spread over the k-step; 4: all in its first half, for the k-step that ends at the barrier, so
+// that the wait in front of the barrier finds them done), in the order of their first use (all of
+// W, then A blocks 0..7); if DMA, two of the wave's 16 DMA instructions per A block (0..7: its A
+// rows, 8..15: its W rows, 8 rows of 128 bytes each).
+// The MFMA is written as inline assembly to accumulate in place: the compiler leaves the
+// destination of this 4-pass instruction free to differ from its accumulator input, which
+// overflows the completely used accumulation registers (the 8-pass 32x32x16 is tied by itself).
+// No accumulator is touched twice within 64 MFMAs, and LDS results reach the operands through
+// the s_waitcnt the compiler places for the asm inputs, so no software-managed hazard arises.
+template <int READS, bool DMA>
+__device__ __forceinline__ void w4_block(f32x4_acc (&acc)[8][8], const W4Frags& cur, W4Frags& nxt,
                                          const bf16* rA, const bf16* rB, int pch,
-                                         __amdgpu_buffer_rsrc_t rs, bf16* lds_rows,
-                                         const uint32_t (&voff)[8], int kbyte) {
+                                         __amdgpu_buffer_rsrc_t rs_a, __amdgpu_buffer_rsrc_t rs_w, bf16* dA,
+                                         bf16* dB, const uint32_t (&voff)[8], int kbyte) {
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
-    const int i = s >> 1, j0 = (s & 1) * 2;
-    constexpr int kIsA = 0xE4;
-    constexpr int kIdx = (0 << 0) | (1 << 2) | (0 << 4) | (2 << 6) | (3 << 8) | (1 << 10) | (2 << 12) | (3 << 14);
 #pragma unroll
-    for (int q = 0; q < (EARLY ? 2 : 1); ++q) {
-      const int rs = EARLY ? 2 * s + q : s;
-      if (rs < 8) {
-        const int idx = (kIdx >> (2 * rs)) & 3;
-        if ((kIsA >> rs) & 1) nxt.a[idx] = *reinterpret_cast<const bf16x8*>(rA + idx * 32 * kBK + pch);
-        else nxt.b[idx] = *reinterpret_cast<const bf16x8*>(rB + idx * 32 * kBK + pch);
+    for (int j = 0; j < 8; ++j) {
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[s][j]) : "v"(cur.b[j]), "v"(cur.a[s]));
+      if (j < READS) {
+        const int r = s * READS + j;
+        if (r < 16) {
+          if (r < 8) nxt.b[r] = *reinterpret_cast<const bf16x8*>(rB + r * 16 * kBK + pch);
+          else nxt.a[r - 8] = *reinterpret_cast<const bf16x8*>(rA + (r - 8) * 16 * kBK + pch);
+        }
       }
+      if (DMA && (j == 4 || j == 6)) {
+        const int d = 2 * s + (j == 6);
+        if (d < 8) w4_dma(rs_a, dA + d * 8 * kBK, voff[d], kbyte);
+        else w4_dma(rs_w, dB + (d - 8) * 8 * kBK, voff[d - 8], kbyte);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    acc[i][j0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[j0], cur.a[i], acc[i][j0], 0, 0, 0);
-    acc[i][j0 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[j0 + 1], cur.a[i], acc[i][j0 + 1], 0, 0, 0);
-    if (DMA) w4_dma(rs, lds_rows + s * 8 * kBK, voff[s], kbyte);
-    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -359,70 +368,71 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
     voff_warm = wave == 0 ? (uint32_t)(lane * 4 * K * 2) : lane < 32 ? (uint32_t)(wrow * K * 2) : kOffOutOfRange;
   }
 
-  f32x16 acc[4][4];
+  f32x4_acc acc[8][8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
-  // MFMA fragment addresses: lane reads row (lane%32) of each 32-row block, k-chunk 2*kk + lane/32
-  // of k-step kk, at its swizzled position.
-  const int frag_row = lane & 31, half = lane >> 5;
+  // MFMA fragment addresses: lane reads row (lane%16) of each 16-row block, k-chunk 4*ks + lane/16
+  // of k-step ks, at its swizzled position.
+  const int frag_row = lane & 15, quad = lane >> 4;
   const int key = (lane >> 1) & 7;
-  int pch[4];
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) pch[kk] = ((kk * 2 + half) ^ key) << 3;
+  const int pch0 = ((0 + quad) ^ key) << 3, pch1 = ((4 + quad) ^ key) << 3;
   const bf16* const rA0 = sA0 + (wm * 128 + frag_row) * kBK;
   const bf16* const rA1 = sA1 + (wm * 128 + frag_row) * kBK;
   const bf16* const rB0 = sB0 + (wn * 128 + frag_row) * kBK;
   const bf16* const rB1 = sB1 + (wn * 128 + frag_row) * kBK;
 
-  // Prologue: k-tile 0 into stage 0 (awaited), the A rows of k-tile 1 into stage 1 (in flight).
+#define W4_WARM(u)                                                                                            \
+  __builtin_amdgcn_raw_ptr_buffer_load_lds((u) < kt_count ? rsrc_warm : rsrc_none,                            \
+                                           (__attribute__((address_space(3))) void*)warm, 4, voff_warm,       \
+                                           kbyte0 + (u) * kBK * 2 + ((warm_id - (u)) & warm_mask) * K * 2, 0, 0)
+  // Prologue: k-tile 0 into stage 0 (awaited), k-tile 1 into stage 1 (in flight), then one warm-up
+  // load, so that "all but one" is the right wait from the first barrier on.
 #pragma unroll
   for (int s = 0; s < 8; ++s) w4_dma(rsrc_a, dA0 + s * 8 * kBK, voff[s], kbyte0);
 #pragma unroll
   for (int s = 0; s < 8; ++s) w4_dma(rsrc_w, dB0 + s * 8 * kBK, voff[s], kbyte0);
   {
-    const __amdgpu_buffer_rsrc_t ra1 = kt_count > 1 ? rsrc_a : rsrc_none;
+    const __amdgpu_buffer_rsrc_t ra1 = kt_count > 1 ? rsrc_a : rsrc_none, rw1 = kt_count > 1 ? rsrc_w : rsrc_none;
 #pragma unroll
     for (int s = 0; s < 8; ++s) w4_dma(ra1, dA1 + s * 8 * kBK, voff[s], kbyte0 + kBK * 2);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) w4_dma(rw1, dB1 + s * 8 * kBK, voff[s], kbyte0 + kBK * 2);
   }
-  __builtin_amdgcn_s_waitcnt(kWaitVm8);
+  W4_WARM(kWarmAhead - 1);
+  __builtin_amdgcn_s_waitcnt(kWaitVm17);
   w4_barrier();
   W4Frags f0, f1;
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    f0.a[s] = *reinterpret_cast<const bf16x8*>(rA0 + s * 32 * kBK + pch[0]);
-    f0.b[s] = *reinterpret_cast<const bf16x8*>(rB0 + s * 32 * kBK + pch[0]);
+  for (int s = 0; s < 8; ++s) {
+    f0.b[s] = *reinterpret_cast<const bf16x8*>(rB0 + s * 16 * kBK + pch0);
+    f0.a[s] = *reinterpret_cast<const bf16x8*>(rA0 + s * 16 * kBK + pch0);
   }
   __builtin_amdgcn_sched_barrier(0);
 
-  // k-tile t on stage c (the other stage: o).  On entry f0 holds k-step 0 of tile t and the A rows
-  // of tile t+1 are in flight to stage o.  k-step 0 adds the W rows of tile t+1 and the warm-up
-  // load for tile t+3; after k-step 2 everything but that load must have landed; the barrier tells
-  // all waves that tile t+1 is complete and stage c is free; k-step 3 (fed from registers) refills
-  // stage c with the A rows of tile t+2 and starts reading tile t+1.
+  // k-tile t on stage c (the other stage: o).  On entry f0 holds k-step 0 of tile t and tile t+1 is
+  // in flight to stage o.  k-step 0 reads k-step 1's fragments; then everything but the last
+  // warm-up load must have landed; the barrier tells all waves that tile t+1 is complete and stage
+  // c is free; k-step 1 (fed from registers) refills stage c with tile t+2, asks for the wave's
+  // share of tile t+3's lines, and starts reading tile t+1.
 #define W4_TILE(t, c, o)                                                                                      \
   {                                                                                                           \
-    const int t1_ = (t) + 1, t2_ = (t) + 2, tw_ = (t) + kWarmAhead;                                           \
-    w4_block<true>(acc, f0, f1, rA##c, rB##c, pch[1], t1_ < kt_count ? rsrc_w : rsrc_none, dB##o, voff,       \
-                   kbyte0 + t1_ * kBK * 2);                                                                   \
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(tw_ < kt_count ? rsrc_warm : rsrc_none,                          \
-                                             (__attribute__((address_space(3))) void*)warm, 4, voff_warm,     \
-                                             kbyte0 + tw_ * kBK * 2 + ((warm_id - tw_) & warm_mask) * K * 2, 0, 0); \
-    __builtin_amdgcn_sched_barrier(0);                                                                        \
-    w4_block<false>(acc, f1, f0, rA##c, rB##c, pch[2], rsrc_none, dB##o, voff, 0);                            \
-    w4_block<false, true>(acc, f0, f1, rA##c, rB##c, pch[3], rsrc_none, dB##o, voff, 0);                      \
+    const int t2_ = (t) + 2;                                                                                  \
+    w4_block<4, false>(acc, f0, f1, rA##c, rB##c, pch1, rsrc_none, rsrc_none, dA##c, dB##c, voff, 0);         \
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);                                                                   \
     __builtin_amdgcn_s_waitcnt(kWaitVm1);                                                                     \
     w4_barrier();                                                                                             \
-    w4_block<true>(acc, f1, f0, rA##o, rB##o, pch[0], t2_ < kt_count ? rsrc_a : rsrc_none, dA##c, voff,       \
-                   kbyte0 + t2_ * kBK * 2);                                                                   \
+    w4_block<2, true>(acc, f1, f0, rA##o, rB##o, pch0, t2_ < kt_count ? rsrc_a : rsrc_none,                   \
+                      t2_ < kt_count ? rsrc_w : rsrc_none, dA##c, dB##c, voff, kbyte0 + t2_ * kBK * 2);       \
+    W4_WARM((t) + kWarmAhead);                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                                                        \
   }
   // Eight k-tiles per trip: the taken branch at the end of a trip costs the matrix pipe about 200
-  // cycles (measured: 2120 cycles for a k-tile inside a trip, 2320 for the one across the branch).
+  // cycles.
   int t = 0;
   for (; t + 7 < kt_count; t += 8) {
     W4_TILE(t, 0, 1);
@@ -440,39 +450,39 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
   }
   if (t < kt_count) W4_TILE(t, 0, 1);
 #undef W4_TILE
+#undef W4_WARM
   __builtin_amdgcn_s_waitcnt(kWaitVm0);      // the trailing (empty) DMA writes have landed
   __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
   w4_barrier();                              // before the stages are reused for the epilogue
 
-  // Epilogue.  The MFMAs take the W fragment as their row operand, so each 32x32 accumulator is a
-  // block of C^T: lane l holds output row m = l%32 and, per register quad a, the four consecutive
-  // columns n = 8a + 4*(l/32) + (0..3).  The wave stages its block through its own 32 KB of the
-  // (now idle) LDS stages so that global memory sees whole row segments of 128-256 bytes.  Global
-  // accesses go through a buffer descriptor over the wave's valid rows (rows past M fall outside
-  // it, columns past N get an out-of-range offset): no branches, so the stores -- and the residual
-  // reads, 16 row segments at a time -- are in flight together instead of one after the other.
+  // Epilogue.  The MFMAs take the W fragment as their row operand, so each 16x16 accumulator is a
+  // block of C^T: accumulator [i][j] of lane l holds output row m = 16i + l%16 and the four
+  // consecutive columns n = 16j + 4*(l/16) + (0..3).  The wave stages its block through its own
+  // 32 KB of the (now idle) LDS stages so that global memory sees whole row segments of 128-256
+  // bytes.  Global accesses go through a buffer descriptor over the wave's valid rows (rows past M
+  // fall outside it, columns past N get an out-of-range offset): no branches, so the stores -- and
+  // the residual reads, 16 row segments at a time -- are in flight together instead of one after
+  // the other.
   bf16* region = wave == 0 ? sA0 : wave == 1 ? sA1 : wave == 2 ? sB0 : sB1;
   const int rows_valid = __builtin_amdgcn_readfirstlane(min(128, max(0, M - m0 - wm * 128)));
   if (SWIGLU) {
-    // Outputs n0 + 64*wn + (0..63): staged as [128 rows][8 chunks of 8 bf16], chunk c of row r at
-    // position c ^ ((r>>1)&7).
+    // Accumulators [i][0..3] are gate, [i][4..7] up of outputs n0 + 64*wn + (0..63): staged as
+    // [128 rows][8 chunks of 8 bf16], chunk c of row r at position c ^ ((r>>1)&7).
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = i * 32 + frag_row;
+    for (int i = 0; i < 8; ++i) {
+      const int row = i * 16 + frag_row;
       const int rkey = (row >> 1) & 7;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < 4; ++j) {
+        bf16x4 v;
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          bf16x4 v;
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const float g = static_cast<float>(static_cast<bf16>(acc[i][j][4 * a + b]));
-            const float u = static_cast<float>(static_cast<bf16>(acc[i][2 + j][4 * a + b]));
-            v[b] = static_cast<bf16>(silu_mul_f32(g, u));
-          }
-          *reinterpret_cast<bf16x4*>(region + row * 64 + (((j * 4 + a) ^ rkey) << 3) + 4 * half) = v;
+        for (int b = 0; b < 4; ++b) {
+          const float g = static_cast<float>(static_cast<bf16>(acc[i][j][b]));
+          const float u = static_cast<float>(static_cast<bf16>(acc[i][4 + j][b]));
+          v[b] = static_cast<bf16>(silu_mul_f32(g, u));
         }
+        *reinterpret_cast<bf16x4*>(region + row * 64 + (((2 * j + (quad >> 1)) ^ rkey) << 3) + 4 * (quad & 1)) = v;
+      }
     }
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);     // own wave's LDS writes have landed; no other wave touches the region
     bf16* cb = reinterpret_cast<bf16*>(Cout) + (int64_t)(m0 + wm * 128) * N;
@@ -489,18 +499,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
   } else if (EPI == kEpiBf16) {
     // [128 rows][16 chunks of 8 bf16], chunk c of row r at position c ^ (r & 15).
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = i * 32 + frag_row;
+    for (int i = 0; i < 8; ++i) {
+      const int row = i * 16 + frag_row;
       const int rkey = row & 15;
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < 8; ++j) {
+        bf16x4 v;
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          bf16x4 v;
-#pragma unroll
-          for (int b = 0; b < 4; ++b) v[b] = static_cast<bf16>(acc[i][j][4 * a + b]);
-          *reinterpret_cast<bf16x4*>(region + row * 128 + (((j * 4 + a) ^ rkey) << 3) + 4 * half) = v;
-        }
+        for (int b = 0; b < 4; ++b) v[b] = static_cast<bf16>(acc[i][j][b]);
+        *reinterpret_cast<bf16x4*>(region + row * 128 + (((2 * j + (quad >> 1)) ^ rkey) << 3) + 4 * (quad & 1)) = v;
+      }
     }
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
     bf16* cb = reinterpret_cast<bf16*>(Cout) + (int64_t)(m0 + wm * 128) * N;
@@ -534,18 +542,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
           x[it] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rc, cbyte, it * 4 * N * 4, 0));
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = i * 32 + frag_row;
+      for (int i = 0; i < 8; ++i) {
+        const int row = i * 16 + frag_row;
         const int rkey = row & 15;
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
+        for (int jj = 0; jj < 4; ++jj) {
+          f32x4 v;
 #pragma unroll
-          for (int a = 0; a < 4; ++a) {
-            f32x4 v;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) v[b] = acc[i][jp * 2 + jj][4 * a + b];
-            *reinterpret_cast<f32x4*>(stage + row * 64 + (((jj * 8 + 2 * a + half) ^ rkey) << 2)) = v;
-          }
+          for (int b = 0; b < 4; ++b) v[b] = acc[i][jp * 4 + jj][b];
+          *reinterpret_cast<f32x4*>(stage + row * 64 + (((jj * 4 + quad) ^ rkey) << 2)) = v;
+        }
       }
       __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
 #pragma unroll
