@@ -288,7 +288,7 @@ fp_status fp_sched_round(fp_sched* sched, double now, fp_sched_decision* decisio
 double fp_sched_predict(const fp_sched* sched, int64_t n_tokens);
 
 /* Diagnostic for the roofline report: runs a register-only loop of the bf16 MFMA instruction the
- * GEMM and attention kernels use (random operands, two waves per SIMD on every CU) for about
+ * GEMM kernel uses (16x16x32; random operands, two waves per SIMD on every CU) for about
  * `milliseconds` and writes the rate of the last launch, in TFLOP/s, to *tflops_out (host).  This
  * is what the matrix pipes sustain on the chip at hand at the clock it holds under that load.
  * Allocates and frees a small device buffer; synchronises `hip_stream`.                          */

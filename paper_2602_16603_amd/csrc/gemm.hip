@@ -764,42 +764,49 @@ void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, in
 
 // ------------------------------------------------------------------------------------------
 // Diagnostic: what the matrix pipes sustain on this chip with nothing else in the way -- a loop of
-// v_mfma_f32_32x32x16_bf16 on eight independent accumulators from registers, random operands
-// (the data the pipes chew on changes the power they draw, and with it the clock), two waves per
-// SIMD on every CU.  The GEMM and attention kernels are judged against this as well as against
-// the vendor peak.
+// v_mfma_f32_16x16x32_bf16 (the instruction of the GEMM; on random operands it sustains about 12 %
+// more than v_mfma_f32_32x32x16_bf16, which attention uses) on 32 independent accumulators from
+// registers, random operands (the data the pipes chew on changes the power they draw, and with it
+// the clock), two waves per SIMD on every CU.  The GEMM and attention kernels are judged against
+// this as well as against the vendor peak.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(512) void mfma_ceiling_kernel(float* __restrict__ sink, int iters) {
-  f32x16 acc[8];
+  f32x4_acc acc[32];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < 32; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-  bf16x8 a, b;
+    for (int r = 0; r < 4; ++r) acc[i][r] = 0.f;
+  bf16x8 a[4], b[8];
   uint32_t h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    h = h * 1664525u + 1013904223u;
-    a[e] = static_cast<bf16>((float)((h >> 8) & 0xFFFF) / 65536.0f - 0.5f);
-    h = h * 1664525u + 1013904223u;
-    b[e] = static_cast<bf16>((float)((h >> 8) & 0xFFFF) / 65536.0f - 0.5f);
+  for (int f = 0; f < 12; ++f) {
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      h = h * 1664525u + 1013904223u;
+      v[e] = static_cast<bf16>((float)((h >> 8) & 0xFFFF) / 65536.0f - 0.5f);
+    }
+    if (f < 4) a[f] = v; else b[f - 4] = v;
   }
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        acc[i * 8 + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i * 8 + j], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < 32; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s += acc[i][r];
+    for (int r = 0; r < 4; ++r) s += acc[i][r];
   sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
 }
 
 // Launches the loop on `blocks` workgroups of 8 waves; returns the FLOPs one launch performs.
 double launch_mfma_ceiling(float* sink, int blocks, int iters, hipStream_t s) {
   mfma_ceiling_kernel<<<dim3((unsigned)blocks), 512, 0, s>>>(sink, iters);
-  return (double)blocks * 8.0 * (double)iters * 8.0 * 2.0 * 32.0 * 32.0 * 16.0;
+  return (double)blocks * 8.0 * (double)iters * 32.0 * 2.0 * 16.0 * 16.0 * 32.0;
 }
 
 }  // namespace fp
