@@ -454,6 +454,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
   __builtin_amdgcn_s_waitcnt(kWaitVm0);      // the trailing (empty) DMA writes have landed
   __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
   w4_barrier();                              // before the stages are reused for the epilogue
+  // The compiler does not know that the assembly above writes the accumulators with MFMA latency:
+  // keep the first read of them away from the last MFMA by more than any such hazard asks for
+  // (the waits and the barrier above already take longer; this makes it independent of them).
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
   // Epilogue.  The MFMAs take the W fragment as their row operand, so each 16x16 accumulator is a
   // block of C^T: accumulator [i][j] of lane l holds output row m = 16i + l%16 and the four
