@@ -1,7 +1,8 @@
 // Dense projections of the prefill layer: C[M,N] = A[M,K] * W[N,K]^T (both operands K-major),
 // FlowPrefill Eq. (1) and the operators qkv_proj / o_proj / gate_up_proj / down_proj of
-// Section 5.1.  bf16 path: MFMA 32x32x16 tiles with fp32 accumulation, LDS-staged and
-// double-buffered.  fp32 path: a plain LDS-tiled FMA kernel (debug).
+// Section 5.1.  bf16 path: MFMA tiles with fp32 accumulation, LDS-staged and double-buffered (the
+// fast kernel on 16x16x32, the small-problem kernel on 32x32x16).  fp32 path: a plain LDS-tiled
+// FMA kernel (debug).
 #include <algorithm>
 
 #include "common.h"
@@ -34,7 +35,7 @@ __device__ __forceinline__ void tile_of_workgroup(int wg, int tiles_m, int tiles
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16 MFMA GEMM.  WGM x WGN waves; each wave owns a (BM/WGM)x(BN/WGN) block of 32x32 MFMA
+// bf16 MFMA GEMM for tiny or odd-K problems (register-staged loads).  WGM x WGN waves; each wave owns a (BM/WGM)x(BN/WGN) block of 32x32 MFMA
 // accumulators.  K is consumed 64 at a time.  LDS rows hold 64 bf16 = eight 16-byte chunks.  The
 // gfx950 LDS has 64 four-byte banks (256 B per clock for reads); a ds_read_b128 is served one
 // half-wave after the other and a half-wave costs max(2, most lanes on one 16-byte bank group)
