@@ -35,8 +35,8 @@ __device__ __forceinline__ void tile_of_workgroup(int wg, int tiles_m, int tiles
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16 MFMA GEMM for tiny or odd-K problems (register-staged loads).  WGM x WGN waves; each wave owns a (BM/WGM)x(BN/WGN) block of 32x32 MFMA
-// accumulators.  K is consumed 64 at a time.  LDS rows hold 64 bf16 = eight 16-byte chunks.  The
+// bf16 MFMA GEMM for tiny or odd-K problems (register-staged loads).  WGM x WGN waves; each wave
+// owns a (BM/WGM)x(BN/WGN) block of 32x32 MFMA accumulators.  K is consumed 64 at a time.  LDS rows hold 64 bf16 = eight 16-byte chunks.  The
 // gfx950 LDS has 64 four-byte banks (256 B per clock for reads); a ds_read_b128 is served one
 // half-wave after the other and a half-wave costs max(2, most lanes on one 16-byte bank group)
 // clocks.  Two consecutive 128-byte rows fill one bank period, so chunk c of row r is stored at
@@ -369,14 +369,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
     voff_warm = wave == 0 ? (uint32_t)(lane * 4 * K * 2) : lane < 32 ? (uint32_t)(wrow * K * 2) : kOffOutOfRange;
   }
 
-  f32x4_acc acc[8][8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
-
   // MFMA fragment addresses: lane reads row (lane%16) of each 16-row block, k-chunk 4*ks + lane/16
   // of k-step ks, at its swizzled position.
   const int frag_row = lane & 15, quad = lane >> 4;
@@ -405,6 +397,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
     for (int s = 0; s < 8; ++s) w4_dma(rw1, dB1 + s * 8 * kBK, voff[s], kbyte0 + kBK * 2);
   }
   W4_WARM(kWarmAhead - 1);
+  __builtin_amdgcn_sched_barrier(0);
+  // Cleared while the first k-tile is on its way.
+  f32x4_acc acc[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) asm volatile("" : "+a"(acc[i][j]));   // materialise the zeros here, not at first use
+  __builtin_amdgcn_sched_barrier(0);
   __builtin_amdgcn_s_waitcnt(kWaitVm17);
   w4_barrier();
   W4Frags f0, f1;
