@@ -25,7 +25,10 @@ namespace fp {
 // each lane one query column and 16 key rows per 32-key block, so the row maximum and row sum of
 // the softmax are in-lane reductions plus one exchange with lane^32 (v_permlane32_swap), the
 // rescale factor is a per-lane scalar, and exp(S^T) converted to bf16 is already laid out as the
-// B operand of the second MFMA, O^T += V^T P^T -- no LDS round trip for P.
+// B operand of the second MFMA, O^T += V^T P^T -- no LDS round trip for P.  The row sum is taken
+// over those bf16 values (the denominator then matches the numerator's weights exactly), one
+// two-element dot product per packed pair; the row maximum takes one three-operand max per two
+// scores.  Every VALU instruction costs issue cycles next to the other wave's MFMAs.
 //
 // Accumulator row i = 8a + 4h + b (a = reg/4, h = lane/32, b = reg%4) of a 32-row block, while
 // the B operand wants k = 8h + e.  Loading key pi(i) into MFMA row i, pi = swap of bits 2 and 3,
@@ -56,6 +59,18 @@ __device__ __forceinline__ float xhalf_max(float v) {
 __device__ __forceinline__ float xhalf_sum(float v) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+// acc + a + b on a packed bf16 pair (v_dot2c_f32_bf16 against (1, 1)).
+__device__ __forceinline__ float pair_sum(bf16 a, bf16 b, float acc) {
+  const bf16x2 p = {a, b};
+  const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+  return __builtin_amdgcn_fdot2_f32_bf16(p, one, acc, false);
 }
 
 // LDS swizzle key of the K tile as a function of the MFMA row (= lane & 31) that reads it.
@@ -194,7 +209,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
   float m_use = -INFINITY;      // exponent reference of this lane's query (exp2 units)
-  float l_run = 0.f;            // this lane's half of the row sum
+  float l_run = 0.f, l_run2 = 0.f;   // this lane's half of the row sum, in two running parts
   // -m_use in all 16 accumulator slots: the score MFMAs start from it, so they deliver s - m_use,
   // the exp2 argument, directly.  Rewritten only when the reference moves.
   f32x16 neg_m;
@@ -239,12 +254,13 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
       }
       // sacc = s - m_use.  The first tile (m_use = -inf encoded as neg_m = 0) and any tile whose
       // row maximum exceeds the reference by more than the head-room move the reference.
-      float mx = -INFINITY;
+      float mx0 = -INFINITY, mx1 = -INFINITY;         // one three-operand max per two scores
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) mx = fmaxf(mx, fmaxf(sacc[rb][r], sacc[rb][r + 1]));
-      mx = xhalf_max(mx);
+      for (int r = 0; r < 16; r += 2) {
+        mx0 = max3(mx0, sacc[0][r], sacc[0][r + 1]);
+        mx1 = max3(mx1, sacc[1][r], sacc[1][r + 1]);
+      }
+      const float mx = xhalf_max(fmaxf(mx0, mx1));
       // Key 0 is visible to every query, so mx is finite from the first tile on.
       if (__any(m_use == -INFINITY || mx > lazy_gap)) {
         const float shift = m_use == -INFINITY ? mx : fmaxf(mx, 0.f);   // new reference - old reference
@@ -252,6 +268,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
         const float alpha = m_use == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(-shift);
         m_use = base + shift;
         l_run *= alpha;
+        l_run2 *= alpha;
 #pragma unroll
         for (int i = 0; i < DB; ++i)
 #pragma unroll
@@ -263,7 +280,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) neg_m[r] = -m_use;
       }
-      float psum = 0.f;
+      // The row sum is taken over the bf16-rounded probabilities, the values P V multiplies by:
+      // one two-element dot product with (1, 1) per packed pair instead of one add per score.
       bf16x8 pf[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
@@ -271,10 +289,11 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) pv[e] = __builtin_amdgcn_exp2f(sacc[c >> 1][8 * (c & 1) + e]);
         pf[c] = __builtin_convertvector(pv, bf16x8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) psum += pv[e];
+        l_run = pair_sum(pf[c][0], pf[c][1], l_run);
+        l_run2 = pair_sum(pf[c][2], pf[c][3], l_run2);
+        l_run = pair_sum(pf[c][4], pf[c][5], l_run);
+        l_run2 = pair_sum(pf[c][6], pf[c][7], l_run2);
       }
-      l_run += psum;
 #pragma unroll
       for (int i = 0; i < DB; ++i) {
         const int d = i * 32 + lq;
@@ -315,7 +334,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(
   // ---- normalise, stage through LDS, store rows with 16-byte accesses ----
   bf16* stage = ((wave >> 1) == 0 ? sK0 : (wave >> 1) == 1 ? sK1 : (wave >> 1) == 2 ? sK2 : sV0) + (wave & 1) * (32 * D);
   {
-    const float l_tot = xhalf_sum(l_run);
+    const float l_tot = xhalf_sum(l_run + l_run2);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
 #pragma unroll
     for (int i = 0; i < DB; ++i)
