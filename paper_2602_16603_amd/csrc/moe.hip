@@ -114,10 +114,16 @@ __global__ __launch_bounds__(256) void moe_plan_kernel(int32_t* __restrict__ pla
   const int e = threadIdx.x;
   int total = 0;
   if (e < n_experts)
-    for (int b = 0; b < n_blocks; ++b) {
-      const int c = block_counts[(int64_t)b * n_experts + e];
-      block_counts[(int64_t)b * n_experts + e] = total;
-      total += c;
+    for (int b0 = 0; b0 < n_blocks; b0 += 16) {    // 16 loads in flight, then their prefix, then 16 stores
+      int c[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        c[i] = b0 + i < n_blocks ? block_counts[(int64_t)(b0 + i) * n_experts + e] : 0;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        if (b0 + i < n_blocks) block_counts[(int64_t)(b0 + i) * n_experts + e] = total;
+        total += c[i];
+      }
     }
   s_cnt[e] = total;
   __syncthreads();
