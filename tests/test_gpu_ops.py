@@ -82,6 +82,46 @@ def test_gemm_fast_path_trip_counts_and_ragged_edges(residual, m, n, k):
     assert torch.all(buf[m:] == 7.0)
 
 
+def _random_gemm_shapes(count, seed):
+    import random
+    rng = random.Random(seed)
+    ms = [1, 7, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 511, 513, 777, 1024, 1500, 2049, 2560, 3001]
+    ns = [8, 16, 64, 120, 128, 136, 248, 256, 264, 512, 520, 1000, 1024, 2048, 2056, 3072, 4104]
+    ks = [8, 16, 24, 64, 72, 128, 192, 256, 320, 512, 1024, 1088, 2048, 4096]
+    out = []
+    while len(out) < count:
+        m, n, k = rng.choice(ms), rng.choice(ns), rng.choice(ks)
+        if m * n * k <= 6e9:
+            out.append((m, n, k, rng.random() < 0.5))
+    return out
+
+
+@pytest.mark.parametrize("m,n,k,residual", _random_gemm_shapes(32, 20260216))
+def test_gemm_seeded_random_shapes(m, n, k, residual):
+    """Shapes drawn (seeded) across every dispatch of the bf16 GEMM -- the small-problem kernel,
+    split-K with its reduction, the 256x256-tile kernel -- with ragged rows, columns and K; rows
+    before and behind the output must stay untouched."""
+    B = _binding()
+    print(f"gemm random m={m} n={n} k={k} residual={residual}", flush=True)
+    a = I.normal_tensor((m, k), 1.0, 31, torch.bfloat16, "cuda")
+    w = I.normal_tensor((n, k), 0.05, 32, torch.bfloat16, "cuda")
+    td = torch.float32 if residual else torch.bfloat16
+    g = 3
+    buf = torch.full((m + 2 * g, n), 7.0, dtype=td, device="cuda")
+    if residual:
+        buf[g:g + m] = I.normal_tensor((m, n), 1.0, 33, torch.float32, "cuda")
+    x0 = buf[g:g + m].clone()
+    out = buf[g:g + m]
+    torch.cuda.synchronize()
+    B.fp_op_gemm(1, a.data_ptr(), w.data_ptr(), out.data_ptr(), m, n, k, residual)
+    torch.cuda.synchronize()
+    ref = O.linear(a.cpu(), w.cpu())
+    if residual:
+        ref = ref + x0.cpu().double()
+    assert max_rel_err(out, ref) <= TOL["bf16"]
+    assert torch.all(buf[:g] == 7.0) and torch.all(buf[g + m:] == 7.0)
+
+
 @pytest.mark.parametrize("name", ["bf16", "fp32"])
 @pytest.mark.parametrize("t,d", [(1, 256), (77, 4096), (5, 5120), (3, 8200), (2, 20000)])
 def test_rmsnorm_matches_definition(name, t, d):
