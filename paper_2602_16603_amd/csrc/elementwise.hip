@@ -130,14 +130,14 @@ void launch_silu_mul(int dtype, const void* gu, void* out, int64_t t, int64_t f,
 
 // ------------------------------------------------------------------------------------------
 // Rotary embedding + paged KV-cache write, one launch.
-//   workgroups [0, T):            one token each -- rotate its Hq query heads in place in the
-//                                 qkv buffer, rotate its Hkv key heads and store them into the
-//                                 K pool [layer][block][Hkv][16][D];
-//   workgroups [T, T+n_kv_items): one (sequence, logical block) each -- copy the raw values of
+//   the first n_kv_items workgroups: one (sequence, logical block) each -- copy the raw values of
 //                                 that block's new tokens into the V pool
 //                                 [layer][block][Hkv][D][16] (transposed inside the block so the
 //                                 attention kernel can read 8 consecutive keys of one channel
-//                                 as a 16-byte MFMA operand).
+//                                 as a 16-byte MFMA operand); they take longest and go first;
+//   the following T workgroups:   one token each -- rotate its Hq query heads in place in the
+//                                 qkv buffer, rotate its Hkv key heads and store them into the
+//                                 K pool [layer][block][Hkv][16][D].
 // Pair (j, j+D/2) is rotated by angle pos * theta^(-2j/D); cos/sin come from a table computed in
 // fp64 on the host.
 // ------------------------------------------------------------------------------------------
@@ -153,8 +153,9 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(
   const int tid = threadIdx.x;
   const int half = head_dim / 2;
   const int64_t width = (int64_t)(n_q_heads + 2 * n_kv_heads) * head_dim;
-  if ((int)blockIdx.x < n_tokens) {
-    const int t = blockIdx.x;
+  const int n_kv_items = (int)gridDim.x - n_tokens;
+  if ((int)blockIdx.x >= n_kv_items) {
+    const int t = (int)blockIdx.x - n_kv_items;
     const int s = tok_seq[t];
     const int pos = tok_pos[t];
     const int64_t blk = block_tables[(int64_t)s * max_blocks + pos / kKvBlock];
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(
     return;
   }
   // ---- value block role ----
-  const int item = blockIdx.x - n_tokens;
+  const int item = blockIdx.x;
   const int s = kv_items[2 * item];
   const int lb = kv_items[2 * item + 1];
   const int cached = cached_lens[s];
