@@ -106,21 +106,26 @@ typedef struct {
  * FP_ERR_OOM, FP_ERR_DEVICE.                                                                      */
 fp_status fp_model_create(const fp_shape* shape, const fp_layer_weights* layers /*host*/,
                           void* hip_stream, fp_model** out);
-/* Frees the pool, the tables and cached workspaces.  All tasks must have been ended.             */
+/* Frees the pool, the tables, cached workspaces and pooled events.  All tasks must have been
+ * ended: while any task of the model is alive the call frees nothing, leaves the model usable and
+ * sets fp_last_error() (the tasks' buffers live in the model's pools).                            */
 void fp_model_destroy(fp_model* model);
 
 /* KV block allocator of the pool (host bookkeeping only).  fp_kv_alloc writes n distinct free
  * block ids to ids_out (host) or fails with FP_ERR_OOM taking none.  fp_kv_free returns them.    */
 fp_status fp_kv_alloc(fp_model* model, int32_t n, int32_t* ids_out /*host*/);
 fp_status fp_kv_free(fp_model* model, int32_t n, const int32_t* ids /*host*/);
-/* Device base addresses of the K and V pools (layouts above) for inspection by tests.            */
+/* Device base addresses of the whole K and V pools (layouts above; layer 0 first).              */
 fp_status fp_model_kv_pools(const fp_model* model, const void** k_pool /*device*/,
                             const void** v_pool /*device*/);
 
 /* "submit" (Section 4; Alg. 2 submit_new_execution): creates a task for a request set of n_seqs
  * prompts (or prompt chunks) packed token-major.
- *   hidden_in    device [T, hidden] in the storage dtype, T = cu_seqlens[n_seqs]; COPIED into
- *                the benchmark's fp32 residual buffer during this call (caller may reuse it after).
+ *   hidden_in    device [T, hidden] in the storage dtype, T = cu_seqlens[n_seqs]; widened into
+ *                the task's own fp32 residual buffer by a kernel this call enqueues on the
+ *                model's stream WITHOUT waiting for it: the caller keeps hidden_in valid and
+ *                unchanged until the first fp_prefill_advance on the task has returned (or the
+ *                stream has otherwise drained); the library never writes it.
  *   cu_seqlens   host [n_seqs+1], non-decreasing, cu_seqlens[0] = 0.  Empty sequences allowed.
  *   cached_lens  host [n_seqs] tokens of each sequence already in the cache (earlier chunks), or
  *                NULL for all zero.  Token i of sequence s has position cached_lens[s] + i.
@@ -170,12 +175,27 @@ fp_status fp_preempt_wait(fp_prefill* task);
  * cursor with the task's workspace and KV blocks untouched.  FP_ERR_STATE unless parked.         */
 fp_status fp_resume(fp_prefill* task);
 
-/* Cursor = the next operator to run: layer in [0, n_layers], op in [0, 9).  (n_layers, 0) = done. */
+/* Cursor = the next operator to run: layer in [0, n_layers], op in [0, 9).  (n_layers, 0) = done.
+ * The layer/operator cursor is part of the preserved state of a task (Section 4, Execution Pool).
+ * Thread-safe: may be polled from any thread while another one is inside fp_prefill_advance.     */
 fp_status fp_prefill_cursor(const fp_prefill* task, int32_t* layer /*host*/, int32_t* op /*host*/);
 
 /* The fp32 residual stream [T, hidden] (device, owned by the task, valid until fp_prefill_end).
  * After FP_DONE it is the stack's output; at a layer boundary it is that layer's input.          */
 fp_status fp_prefill_hidden(const fp_prefill* task, const void** dev_ptr);
+
+/* The preserved KV state of a task (Section 4, "Execution Pool": a preempted task keeps its
+ * partial KV cache until it is resumed; Section 3.1: later chunks and the decode phase read it):
+ * device base addresses of layer `layer`'s slice of the paged pools,
+ *   *k_pool [kv_num_blocks][Hkv][16][D], *v_pool [kv_num_blocks][Hkv][D][16] (storage dtype),
+ * and the task's block tables, host [n_seqs, max_blocks] (row s, entry b = physical block of
+ * positions 16b..16b+15 of sequence s; max_blocks from fp_prefill_block_tables).  All three stay
+ * owned by the model / the task and are valid until fp_prefill_end.  Blocks of layers the cursor
+ * has not passed yet hold whatever the pool held before.  Does not synchronise: read the device
+ * memory only while the task is not running (parked, idle between advance calls, or done).
+ * FP_ERR_INVALID for a null argument or a layer outside [0, n_layers).                           */
+fp_status fp_prefill_kv(const fp_prefill* task, int32_t layer, const void** k_pool /*device*/,
+                        const void** v_pool /*device*/, const int32_t** block_tables_host);
 
 /* The task's block tables (host [n_seqs, max_blocks], owned by the task) and max_blocks.         */
 fp_status fp_prefill_block_tables(const fp_prefill* task, const int32_t** tables_host,
@@ -223,9 +243,21 @@ void fp_prefill_end(fp_prefill* task);
  *                  list in Section 5.1); same bits as fp_op_gemm followed by fp_op_silu_mul.
  *                  FP_ERR_INVALID for shapes the fused kernel does not take (K % 64, F % 8, fewer
  *                  than 96 output tiles of 256 x 128): callers then use the two-operator form.
+ *   fp_op_gemm_ws  fp_op_gemm with a caller-provided device workspace (256-byte aligned): problems
+ *                  with too few output tiles to fill the chip are then cut over K, the fp32 partial
+ *                  sums go to the workspace and a second kernel adds them in a fixed order -- the
+ *                  form the prefill path uses for the 128-1024-token requests of the evaluation
+ *                  trace (Section 6.1, Table 1).  fp_op_gemm_workspace_bytes says how much such a
+ *                  problem wants (0: it would not be cut); with less, or with fp_op_gemm, the
+ *                  problem runs uncut.  Results of the cut and uncut forms differ by fp32 rounding
+ *                  order only.
  * FP_ERR_INVALID on misaligned or non-positive sizes (K and N multiples of 8).                   */
 fp_status fp_op_gemm(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
                      int64_t k, int32_t residual, void* hip_stream);
+fp_status fp_op_gemm_ws(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
+                        int64_t k, int32_t residual, void* workspace /*device*/,
+                        int64_t workspace_bytes, void* hip_stream);
+int64_t fp_op_gemm_workspace_bytes(int32_t dtype, int64_t m, int64_t n, int64_t k);
 fp_status fp_op_rmsnorm(int32_t dtype, const void* x_f32, const void* gain, void* out,
                         int64_t t, int64_t d, float eps, void* hip_stream);
 fp_status fp_op_silu_mul(int32_t dtype, const void* gu, void* out, int64_t t, int64_t f,

@@ -237,7 +237,8 @@ def moe_selection_shortfall(h: torch.Tensor, w_router: torch.Tensor, ids: torch.
 
 
 def moe_mlp(h: torch.Tensor, w_router: torch.Tensor, w_gate_up: torch.Tensor, w_down: torch.Tensor,
-            top_k: int, forced_ids: Optional[torch.Tensor] = None) -> torch.Tensor:
+            top_k: int, forced_ids: Optional[torch.Tensor] = None,
+            weights_out: Optional[List[torch.Tensor]] = None) -> torch.Tensor:
     """sum_j weight_j * down_e(j)( silu_mul( gate_up_e(j)( h ) ) ) per token.  `forced_ids` [T, k]
     replaces the router's own SELECTION (the weights stay the oracle's own probabilities of those
     experts, renormalised): for checking an implementation whose decision between two experts a
@@ -249,6 +250,8 @@ def moe_mlp(h: torch.Tensor, w_router: torch.Tensor, w_gate_up: torch.Tensor, w_
         wts = moe_weights_for(h, w_router, ids)
     else:
         ids, wts = moe_route(h, w_router, top_k)
+    if weights_out is not None:          # read-out for tests: the weights this layer applied, [T, k]
+        weights_out.append(_f64(wts).clone())
     out = torch.zeros_like(h)
     for e in range(w_gate_up.shape[0]):
         rows, slots = torch.nonzero(ids == e, as_tuple=True)
@@ -283,7 +286,8 @@ class KVState:
 def layer_forward(shape: Shape, w: LayerWeights, x: torch.Tensor, cu_seqlens: Sequence[int],
                   k_prev: List[torch.Tensor], v_prev: List[torch.Tensor],
                   forced_ids: Optional[torch.Tensor] = None,
-                  shortfall_out: Optional[List[torch.Tensor]] = None
+                  shortfall_out: Optional[List[torch.Tensor]] = None,
+                  weights_out: Optional[List[torch.Tensor]] = None
                   ) -> Tuple[torch.Tensor, List[torch.Tensor], List[torch.Tensor]]:
     """One decoder layer over a packed batch.
 
@@ -318,7 +322,7 @@ def layer_forward(shape: Shape, w: LayerWeights, x: torch.Tensor, cu_seqlens: Se
     if w.w_router is not None:
         if forced_ids is not None and shortfall_out is not None:
             shortfall_out.append(moe_selection_shortfall(h2, w.w_router, forced_ids, shape.top_k))
-        x = x + moe_mlp(h2, w.w_router, w.w_gate_up, w.w_down, shape.top_k, forced_ids)
+        x = x + moe_mlp(h2, w.w_router, w.w_gate_up, w.w_down, shape.top_k, forced_ids, weights_out)
     else:
         act = silu_mul(linear(h2, w.w_gate_up))
         x = x + linear(act, w.w_down)
@@ -328,7 +332,8 @@ def layer_forward(shape: Shape, w: LayerWeights, x: torch.Tensor, cu_seqlens: Se
 def prefill(shape: Shape, layers: Sequence[LayerWeights], x: torch.Tensor,
             cu_seqlens: Sequence[int], cache: Optional[KVState] = None,
             forced_ids: Optional[Sequence[torch.Tensor]] = None,
-            shortfall_out: Optional[List[torch.Tensor]] = None) -> Tuple[torch.Tensor, KVState]:
+            shortfall_out: Optional[List[torch.Tensor]] = None,
+            weights_out: Optional[List[torch.Tensor]] = None) -> Tuple[torch.Tensor, KVState]:
     """The whole stack over a packed batch of (chunks of) prompts.  `cache` carries what earlier
     chunks of the same sequences left behind (None = empty).  Returns the final residual stream
     [T, d] and the extended cache."""
@@ -340,7 +345,8 @@ def prefill(shape: Shape, layers: Sequence[LayerWeights], x: torch.Tensor,
     for layer in range(shape.n_layers):
         x, k_l, v_l = layer_forward(shape, layers[layer], x, cu_seqlens,
                                     cache.k[layer], cache.v[layer],
-                                    None if forced_ids is None else forced_ids[layer], shortfall_out)
+                                    None if forced_ids is None else forced_ids[layer], shortfall_out,
+                                    weights_out)
         new_k.append(k_l)
         new_v.append(v_l)
     return x, KVState(k=new_k, v=new_v)

@@ -62,6 +62,7 @@ _SIGS = {
     "fp_resume": (C.c_int, [_P]),
     "fp_prefill_cursor": (C.c_int, [_P, _I32P, _I32P]),
     "fp_prefill_hidden": (C.c_int, [_P, C.POINTER(_P)]),
+    "fp_prefill_kv": (C.c_int, [_P, C.c_int32, C.POINTER(_P), C.POINTER(_P), C.POINTER(_I32P)]),
     "fp_prefill_block_tables": (C.c_int, [_P, C.POINTER(_I32P), _I32P]),
     "fp_prefill_kv_gather": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P]),
     "fp_prefill_set_timing": (C.c_int, [_P, C.c_int32]),
@@ -69,6 +70,8 @@ _SIGS = {
     "fp_prefill_moe_routing": (C.c_int, [_P, C.c_int32, _P, _P]),
     "fp_prefill_end": (None, [_P]),
     "fp_op_gemm": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _P]),
+    "fp_op_gemm_ws": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _P, C.c_int64, _P]),
+    "fp_op_gemm_workspace_bytes": (C.c_int64, [C.c_int32, C.c_int64, C.c_int64, C.c_int64]),
     "fp_op_rmsnorm": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_float, _P]),
     "fp_op_silu_mul": (C.c_int, [C.c_int32, _P, _P, C.c_int64, C.c_int64, _P]),
     "fp_op_gemm_swiglu": (C.c_int, [_P, _P, _P, C.c_int64, C.c_int64, C.c_int64, _P]),
@@ -220,6 +223,13 @@ def fp_prefill_block_tables(task: int, n_seqs: int) -> np.ndarray:
     return np.ctypeslib.as_array(ptr, shape=(n_seqs, mb.value)).copy()
 
 
+def fp_prefill_kv(task: int, layer: int, n_seqs: int):
+    """-> (k_pool address of that layer, v_pool address of that layer, block tables [n_seqs, max_blocks])."""
+    k, v, ptr = _P(), _P(), _I32P()
+    _check(lib.fp_prefill_kv(_P(task), layer, C.byref(k), C.byref(v), C.byref(ptr)), "fp_prefill_kv")
+    return k.value, v.value, fp_prefill_block_tables(task, n_seqs)
+
+
 def fp_prefill_kv_gather(task: int, layer: int, seq: int, k_out: int, v_out: int) -> None:
     _check(lib.fp_prefill_kv_gather(_P(task), layer, seq, _P(k_out), _P(v_out)), "fp_prefill_kv_gather")
 
@@ -243,6 +253,16 @@ def fp_op_gemm(dtype: int, a: int, w: int, c: int, m: int, n: int, k: int, resid
                hip_stream: int = 0) -> None:
     _check(lib.fp_op_gemm(dtype, _P(a), _P(w), _P(c), m, n, k, 1 if residual else 0, _P(hip_stream)),
            "fp_op_gemm")
+
+
+def fp_op_gemm_ws(dtype: int, a: int, w: int, c: int, m: int, n: int, k: int, residual: bool,
+                  workspace: int, workspace_bytes: int, hip_stream: int = 0) -> None:
+    _check(lib.fp_op_gemm_ws(dtype, _P(a), _P(w), _P(c), m, n, k, 1 if residual else 0, _P(workspace),
+                             workspace_bytes, _P(hip_stream)), "fp_op_gemm_ws")
+
+
+def fp_op_gemm_workspace_bytes(dtype: int, m: int, n: int, k: int) -> int:
+    return int(lib.fp_op_gemm_workspace_bytes(dtype, m, n, k))
 
 
 def fp_op_rmsnorm(dtype: int, x_f32: int, gain: int, out: int, t: int, d: int, eps: float,

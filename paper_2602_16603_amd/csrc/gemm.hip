@@ -682,12 +682,12 @@ static void launch_bf16_cfg(const bf16* a, const bf16* w, void* c, int m, int n,
                             hipStream_t s) {
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + BN - 1) / BN;
   const size_t smem = (size_t)2 * (BM + BN) * kBK * sizeof(bf16);
-  static bool attr_set = false;   // per instantiation
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, WGM, WGN, RESID>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    attr_set = true;
-  }
+  // Once per instantiation; a function-local static is initialised exactly once even when several
+  // threads launch at the same time.
+  static const hipError_t attr_set =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, WGM, WGN, RESID>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  (void)attr_set;
   gemm_bf16_kernel<BM, BN, WGM, WGN, RESID><<<dim3((unsigned)(tiles_m * tiles_n)), WGM * WGN * 64, smem, s>>>(
       a, w, c, m, n, k, tiles_m, tiles_n);
 }

@@ -24,6 +24,7 @@
 #include "../../include/flowprefill.h"
 #include "common.h"
 #include "kernels.h"
+#include "task_core.h"
 
 namespace {
 
@@ -58,13 +59,13 @@ void set_last_error(const char* message) { g_last_error = message; }
 namespace {
 
 struct Workspace {
-  void* base = nullptr;
+  void* base = nullptr;        // device
   size_t bytes = 0;
+  void* staging = nullptr;     // pinned host memory the task's metadata is uploaded from
+  size_t staging_bytes = 0;
 };
 
-enum class TaskState { Idle, Running, Parked, Done };
-
-constexpr int kEventRing = 8;
+using fp::kMarkRing;
 
 }  // namespace
 
@@ -78,17 +79,20 @@ struct fp_model {
   float* rope_sin = nullptr;
   void* k_pool = nullptr;
   void* v_pool = nullptr;
-  std::mutex mu;                       // guards free_blocks, ws_cache, live_tasks
+  std::mutex mu;                       // guards free_blocks, ws_cache, the event pools, live_tasks
   std::vector<int32_t> free_blocks;    // stack of free physical block ids
   std::vector<uint8_t> block_used;
   std::vector<Workspace> ws_cache;
+  std::vector<hipEvent_t> marker_events;   // idle completion markers (no timing), reused by later tasks
+  std::vector<hipEvent_t> timing_events;   // idle timing events
   int live_tasks = 0;
 };
 
-struct fp_prefill {
+struct fp_prefill : fp::OpBackend {
+  fp_prefill(int32_t total_ops, uint32_t mask) : core(total_ops, FP_OPS_PER_LAYER, mask) {}
+
   fp_model* model = nullptr;
   int32_t n_tokens = 0, n_seqs = 0, max_blocks = 0;
-  uint32_t boundary_mask = FP_BOUNDARY_EVERY_OP;
   std::vector<int32_t> cu, cached, tables, owned_blocks;
   Workspace ws;
   // carved out of ws:
@@ -103,20 +107,25 @@ struct fp_prefill {
   void* splitk = nullptr;              // split-K partial sums (0 bytes when no GEMM of this task splits)
   size_t splitk_bytes = 0;
   fp::BatchMeta meta{};
-  // cursor and gate
-  int32_t cursor = 0;                  // next operator, 0 .. n_layers*9
-  int32_t launch_ahead = 2;
-  std::mutex mu;
-  std::condition_variable cv;
-  TaskState state = TaskState::Idle;
-  std::atomic<int> signal{0};
-  hipEvent_t ring[kEventRing] = {};
-  hipEvent_t done_ev[kEventRing] = {};   // event that marks the completion of the k-th last operator (not owned)
+  // cursor, launch-ahead bound and preemption gate
+  fp::TaskCore core;
+  hipEvent_t ring[kMarkRing] = {};      // the task's own completion markers (from the model's pool)
+  hipEvent_t slot_ev[kMarkRing] = {};   // event standing for marker slot i (ring[i], or a timing event)
   // per-op timing
   bool timing = false;
-  std::vector<hipEvent_t> tev;          // recorded events, in order
-  std::vector<int32_t> tmark;           // tmark[i] = index in tev of the boundary before operator i of this call
+  std::vector<hipEvent_t> tev;          // timing events of the most recent advance call, in order
+  std::vector<int32_t> tmark;           // tmark[i] = index in tev of the boundary before operator i of that call
   int32_t timed_ops = 0;
+
+  // ---- fp::OpBackend: what the state machine asks of the device ----
+  void begin_call() override;
+  int launch(int32_t index, bool* launched) override;
+  int mark(int slot) override;
+  int wait_mark(int slot) override;
+  int drain() override;
+  bool wants_marks() const override { return timing; }
+  void op_issued(int32_t issued, bool launched) override;
+  hipEvent_t timing_event();
 };
 
 namespace {
@@ -183,7 +192,12 @@ fp_status launch_op(fp_prefill* t, int32_t index) {
   return FP_OK;
 }
 
-fp_status acquire_workspace(fp_model* m, size_t bytes, Workspace* out) {
+// Device workspace + pinned staging for one task.  Workspaces are cached in the model: a request
+// takes the smallest cached one that fits; on a miss every cached one (all too small) is freed
+// before the new allocation, so the cache never holds more than the tasks in flight need.
+fp_status acquire_workspace(fp_model* m, size_t bytes, size_t staging_bytes, Workspace* out) {
+  std::vector<Workspace> drop;
+  Workspace got;
   {
     std::lock_guard<std::mutex> lk(m->mu);
     int best = -1;
@@ -191,15 +205,33 @@ fp_status acquire_workspace(fp_model* m, size_t bytes, Workspace* out) {
       if (m->ws_cache[i].bytes >= bytes && (best < 0 || m->ws_cache[i].bytes < m->ws_cache[best].bytes))
         best = i;
     if (best >= 0) {
-      *out = m->ws_cache[best];
+      got = m->ws_cache[best];
       m->ws_cache.erase(m->ws_cache.begin() + best);
-      return FP_OK;
+    } else {
+      drop.swap(m->ws_cache);
     }
   }
-  void* p = nullptr;
-  FP_HIP(hipMalloc(&p, bytes));
-  out->base = p;
-  out->bytes = bytes;
+  for (auto& w : drop) {          // idle since their task ended (which drained the stream)
+    (void)hipFree(w.base);
+    (void)hipHostFree(w.staging);
+  }
+  if (!got.base) {
+    FP_HIP(hipMalloc(&got.base, bytes));
+    got.bytes = bytes;
+  }
+  if (got.staging_bytes < staging_bytes) {
+    (void)hipHostFree(got.staging);
+    got.staging = nullptr;
+    got.staging_bytes = 0;
+    const size_t want = std::max<size_t>(staging_bytes, 64 << 10);
+    hipError_t e = hipHostMalloc(&got.staging, want, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      (void)hipFree(got.base);
+      return fail(FP_ERR_OOM, "pinned staging buffer: %s", hipGetErrorString(e));
+    }
+    got.staging_bytes = want;
+  }
+  *out = got;
   return FP_OK;
 }
 
@@ -209,7 +241,89 @@ void release_workspace(fp_model* m, Workspace ws) {
   m->ws_cache.push_back(ws);
 }
 
+// Events are pooled in the model: creating and destroying eight of them per task showed up in the
+// time of short requests.
+fp_status acquire_events(fp_model* m, bool with_timing, int n, hipEvent_t* out) {
+  std::vector<hipEvent_t>& pool = with_timing ? m->timing_events : m->marker_events;
+  int got = 0;
+  {
+    std::lock_guard<std::mutex> lk(m->mu);
+    while (got < n && !pool.empty()) { out[got++] = pool.back(); pool.pop_back(); }
+  }
+  for (; got < n; ++got) {
+    hipError_t e = with_timing ? hipEventCreate(&out[got]) : hipEventCreateWithFlags(&out[got], hipEventDisableTiming);
+    if (e != hipSuccess) {
+      for (int i = 0; i < got; ++i) (void)hipEventDestroy(out[i]);
+      return fail(FP_ERR_DEVICE, "event creation: %s", hipGetErrorString(e));
+    }
+  }
+  return FP_OK;
+}
+
+void release_events(fp_model* m, bool with_timing, int n, hipEvent_t* ev) {
+  std::lock_guard<std::mutex> lk(m->mu);
+  std::vector<hipEvent_t>& pool = with_timing ? m->timing_events : m->marker_events;
+  for (int i = 0; i < n; ++i)
+    if (ev[i]) { pool.push_back(ev[i]); ev[i] = nullptr; }
+}
+
 }  // namespace
+
+// ---- the task as the state machine's device backend ----
+hipEvent_t fp_prefill::timing_event() {
+  hipEvent_t ev = nullptr;
+  if (acquire_events(model, true, 1, &ev) != FP_OK) return nullptr;
+  tev.push_back(ev);
+  (void)hipEventRecord(ev, model->stream);
+  return ev;
+}
+
+void fp_prefill::begin_call() {
+  timed_ops = 0;
+  if (!timing) return;
+  release_events(model, true, (int)tev.size(), tev.data());
+  tev.clear();
+  tmark.assign(1, 0);
+  (void)timing_event();
+}
+
+int fp_prefill::launch(int32_t index, bool* launched) {
+  *launched = !(swiglu_fused && index % FP_OPS_PER_LAYER == 7);
+  return launch_op(this, index) == FP_OK ? 0 : -1;
+}
+
+// One event per operator serves both the launch-ahead bound and the timing read-out (an event
+// record costs the device a few microseconds between two kernels).
+int fp_prefill::mark(int slot) {
+  hipEvent_t ev = ring[slot];
+  if (timing) {
+    ev = timing_event();
+    if (!ev) return -1;
+  } else {
+    hipError_t e = hipEventRecord(ev, model->stream);
+    if (e != hipSuccess) { fail(FP_ERR_DEVICE, "event record: %s", hipGetErrorString(e)); return -1; }
+  }
+  slot_ev[slot] = ev;
+  return 0;
+}
+
+int fp_prefill::wait_mark(int slot) {
+  hipError_t e = hipEventSynchronize(slot_ev[slot]);
+  if (e != hipSuccess) { fail(FP_ERR_DEVICE, "event wait: %s", hipGetErrorString(e)); return -1; }
+  return 0;
+}
+
+int fp_prefill::drain() {
+  hipError_t e = hipStreamSynchronize(model->stream);
+  if (e != hipSuccess) { fail(FP_ERR_DEVICE, "stream sync: %s", hipGetErrorString(e)); return -1; }
+  return 0;
+}
+
+void fp_prefill::op_issued(int32_t issued, bool /*launched*/) {
+  if (!timing) return;
+  tmark.push_back((int32_t)tev.size() - 1);
+  timed_ops = issued + 1;
+}
 
 extern "C" {
 
@@ -308,8 +422,21 @@ fp_status fp_model_create(const fp_shape* shape, const fp_layer_weights* layers,
 
 void fp_model_destroy(fp_model* m) {
   if (!m) return;
+  {
+    std::lock_guard<std::mutex> lk(m->mu);
+    if (m->live_tasks > 0) {
+      // Freeing the pools under tasks that still point into them would be a use after free on the
+      // device: refuse, leave the model intact, and say so.
+      char buf[128];
+      snprintf(buf, sizeof(buf), "fp_model_destroy: %d task(s) not ended; model left alive", m->live_tasks);
+      g_last_error = buf;
+      return;
+    }
+  }
   (void)hipStreamSynchronize(m->stream);
-  for (auto& ws : m->ws_cache) (void)hipFree(ws.base);
+  for (auto& ws : m->ws_cache) { (void)hipFree(ws.base); (void)hipHostFree(ws.staging); }
+  for (auto& ev : m->marker_events) (void)hipEventDestroy(ev);
+  for (auto& ev : m->timing_events) (void)hipEventDestroy(ev);
   (void)hipFree(m->rope_cos);
   (void)hipFree(m->rope_sin);
   (void)hipFree(m->k_pool);
@@ -367,12 +494,11 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   if (block_tables && max_blocks <= 0) return fail(FP_ERR_INVALID, "max_blocks must be positive");
   const fp_shape& sh = m->shape;
 
-  fp_prefill* t = new (std::nothrow) fp_prefill();
+  fp_prefill* t = new (std::nothrow) fp_prefill(sh.n_layers * FP_OPS_PER_LAYER, boundary_mask & FP_BOUNDARY_EVERY_OP);
   if (!t) return fail(FP_ERR_OOM, "host allocation failed");
   t->model = m;
   t->n_tokens = T;
   t->n_seqs = n_seqs;
-  t->boundary_mask = boundary_mask & FP_BOUNDARY_EVERY_OP;
   t->cu.assign(cu_seqlens, cu_seqlens + n_seqs + 1);
   t->cached.assign((size_t)n_seqs, 0);
   if (cached_lens) t->cached.assign(cached_lens, cached_lens + n_seqs);
@@ -469,7 +595,7 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   const size_t n_int = tok_seq.size() + tok_pos.size() + t->cu.size() + t->cached.size() +
                        t->tables.size() + kv_items.size() + attn_items.size();
   const size_t o_int = carve((n_int + 16) * 4);
-  fp_status st = acquire_workspace(m, off, &t->ws);
+  fp_status st = acquire_workspace(m, off, (n_int + 16) * 4, &t->ws);
   if (st != FP_OK) {
     if (!t->owned_blocks.empty()) fp_kv_free(m, (int32_t)t->owned_blocks.size(), t->owned_blocks.data());
     delete t;
@@ -486,22 +612,30 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
     t->moe_hp = base + o_mh; t->moe_act = base + o_ma; t->moe_y = base + o_my;
   }
 
-  std::vector<int32_t> ints;
-  ints.reserve(n_int);
-  auto put = [&](const std::vector<int32_t>& v) { size_t at = ints.size(); ints.insert(ints.end(), v.begin(), v.end()); return at; };
+  // Metadata goes through the workspace's pinned staging buffer, so the upload is asynchronous
+  // and nothing here waits for the stream.
+  int32_t* ints = static_cast<int32_t*>(t->ws.staging);
+  size_t n_put = 0;
+  auto put = [&](const std::vector<int32_t>& v) {
+    const size_t at = n_put;
+    if (!v.empty()) memcpy(ints + at, v.data(), v.size() * 4);
+    n_put += v.size();
+    return at;
+  };
   const size_t a_seq = put(tok_seq), a_pos = put(tok_pos), a_cu = put(t->cu), a_cached = put(t->cached),
                a_tab = put(t->tables), a_kv = put(kv_items), a_attn = put(attn_items);
   int32_t* dints = reinterpret_cast<int32_t*>(base + o_int);
   auto bail = [&](fp_status code) {
+    (void)hipStreamSynchronize(m->stream);      // nothing of this task may still be in flight
     release_workspace(m, t->ws);
     if (!t->owned_blocks.empty()) fp_kv_free(m, (int32_t)t->owned_blocks.size(), t->owned_blocks.data());
-    for (auto& ev : t->ring) if (ev) (void)hipEventDestroy(ev);
+    release_events(m, false, kMarkRing, t->ring);
     delete t;
     return code;
   };
   hipError_t he;
-  if (!ints.empty() &&
-      (he = hipMemcpyAsync(dints, ints.data(), ints.size() * 4, hipMemcpyHostToDevice, m->stream)) != hipSuccess)
+  if (n_put &&
+      (he = hipMemcpyAsync(dints, ints, n_put * 4, hipMemcpyHostToDevice, m->stream)) != hipSuccess)
     return bail(fail(FP_ERR_DEVICE, "metadata upload: %s", hipGetErrorString(he)));
   t->meta.n_tokens = T;
   t->meta.n_seqs = n_seqs;
@@ -517,11 +651,9 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   t->meta.n_attn_items = (int32_t)(attn_items.size() / 2);
 
   fp::launch_to_residual(sh.dtype, hidden_in, t->x, (int64_t)T * sh.hidden, m->stream);
-  if ((he = hipGetLastError()) != hipSuccess || (he = hipStreamSynchronize(m->stream)) != hipSuccess)
+  if ((he = hipGetLastError()) != hipSuccess)
     return bail(fail(FP_ERR_DEVICE, "residual initialisation: %s", hipGetErrorString(he)));
-  for (auto& ev : t->ring)
-    if ((he = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess)
-      return bail(fail(FP_ERR_DEVICE, "event creation: %s", hipGetErrorString(he)));
+  if ((st = acquire_events(m, false, kMarkRing, t->ring)) != FP_OK) return bail(st);
   {
     std::lock_guard<std::mutex> lk(m->mu);
     m->live_tasks++;
@@ -531,143 +663,43 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
 }
 
 fp_status fp_prefill_set_launch_ahead(fp_prefill* t, int32_t k) {
-  if (!t || k < 0 || k > kEventRing) return fail(FP_ERR_INVALID, "launch_ahead must be 0..%d", kEventRing);
-  std::lock_guard<std::mutex> lk(t->mu);
-  if (t->state == TaskState::Running) return fail(FP_ERR_STATE, "task is running");
-  t->launch_ahead = k;
-  return FP_OK;
+  if (!t) return fail(FP_ERR_INVALID, "null task");
+  switch (t->core.set_launch_ahead(k)) {
+    case fp::kTaskOk: return FP_OK;
+    case fp::kTaskErrState: return fail(FP_ERR_STATE, "task is running");
+    default: return fail(FP_ERR_INVALID, "launch_ahead must be 0..%d", kMarkRing);
+  }
 }
 
 fp_status fp_prefill_set_timing(fp_prefill* t, int32_t on) {
   if (!t) return fail(FP_ERR_INVALID, "null task");
-  std::lock_guard<std::mutex> lk(t->mu);
-  if (t->state == TaskState::Running) return fail(FP_ERR_STATE, "task is running");
-  t->timing = on != 0;
+  if (!t->core.unless_running([&] { t->timing = on != 0; })) return fail(FP_ERR_STATE, "task is running");
   return FP_OK;
 }
 
 fp_status fp_prefill_advance(fp_prefill* t, int32_t max_ops, int32_t* ops_done) {
   if (!t || max_ops < 0) return fail(FP_ERR_INVALID, "bad argument");
-  if (ops_done) *ops_done = 0;
-  const int32_t total = t->model->shape.n_layers * FP_OPS_PER_LAYER;
-  {
-    std::lock_guard<std::mutex> lk(t->mu);
-    if (t->state != TaskState::Idle)
-      return fail(FP_ERR_STATE, "advance on a task that is %s",
-                  t->state == TaskState::Parked ? "parked" : t->state == TaskState::Done ? "done" : "running");
-    t->state = TaskState::Running;
+  const int r = t->core.advance(*t, max_ops, ops_done);
+  if (r == fp::kTaskErrState) {
+    const fp::TaskState st = t->core.state();
+    return fail(FP_ERR_STATE, "advance on a task that is %s",
+                st == fp::TaskState::Parked ? "parked" : st == fp::TaskState::Done ? "done" : "running");
   }
-  hipStream_t s = t->model->stream;
-  int32_t issued = 0;
-  fp_status result = FP_OK;
-  t->timed_ops = 0;
-  auto finish = [&](TaskState st, bool ack) {
-    std::lock_guard<std::mutex> lk(t->mu);
-    t->state = st;
-    if (ack) t->signal.store(0, std::memory_order_release);
-    t->cv.notify_all();
-  };
-  while (t->cursor < total && issued < max_ops) {
-    // Bound how far the host runs ahead of the device: operator i is launched only once
-    // operator i - launch_ahead has completed.
-    if (t->launch_ahead > 0 && issued >= t->launch_ahead) {
-      hipEvent_t ev = t->done_ev[(issued - t->launch_ahead) % kEventRing];
-      hipError_t e = ev ? hipEventSynchronize(ev) : hipSuccess;
-      if (e != hipSuccess) { result = fail(FP_ERR_DEVICE, "event wait: %s", hipGetErrorString(e)); break; }
-    }
-    // Preemption check at the boundary after the previous operator (Section 5.1).
-    const bool boundary = t->cursor == 0 ||
-                          ((t->boundary_mask >> ((t->cursor - 1) % FP_OPS_PER_LAYER)) & 1u);
-    if (boundary && t->signal.load(std::memory_order_acquire)) {
-      hipError_t e = hipStreamSynchronize(s);
-      if (e != hipSuccess) { result = fail(FP_ERR_DEVICE, "drain: %s", hipGetErrorString(e)); break; }
-      if (ops_done) *ops_done = issued;
-      finish(TaskState::Parked, true);
-      return FP_PREEMPTED;
-    }
-    // One event per operator serves both the launch-ahead bound and the timing read-out (an event
-    // record costs the device a few microseconds between two kernels); an operator that launches
-    // nothing (SiLU*up after the fused gate_up GEMM) records none and completes with its
-    // predecessor.
-    auto timing_event = [&]() -> hipEvent_t {
-      hipEvent_t ev = nullptr;
-      if (hipEventCreate(&ev) != hipSuccess) return nullptr;
-      t->tev.push_back(ev);
-      (void)hipEventRecord(ev, s);
-      return ev;
-    };
-    if (t->timing && issued == 0) {
-      for (auto& ev : t->tev) if (ev) (void)hipEventDestroy(ev);
-      t->tev.clear();
-      t->tmark.assign(1, 0);
-      (void)timing_event();
-    }
-    const bool launches = !(t->swiglu_fused && t->cursor % FP_OPS_PER_LAYER == 7);
-    fp_status st = launch_op(t, t->cursor);
-    if (st != FP_OK) { result = st; break; }
-    hipEvent_t done = issued > 0 ? t->done_ev[(issued - 1) % kEventRing] : nullptr;
-    if (launches) {
-      if (t->timing) {
-        done = timing_event();
-      } else if (t->launch_ahead > 0) {
-        done = t->ring[issued % kEventRing];
-        (void)hipEventRecord(done, s);
-      }
-    }
-    if (t->timing) { t->tmark.push_back((int32_t)t->tev.size() - 1); t->timed_ops = issued + 1; }
-    t->done_ev[issued % kEventRing] = done;
-    t->cursor++;
-    issued++;
-  }
-  hipError_t e = hipStreamSynchronize(s);
-  if (e != hipSuccess && result >= 0) result = fail(FP_ERR_DEVICE, "stream sync: %s", hipGetErrorString(e));
-  if (ops_done) *ops_done = issued;
-  if (result < 0) {
-    finish(TaskState::Idle, false);
-    return result;
-  }
-  if (t->cursor >= total) {
-    finish(TaskState::Done, true);
-    return FP_DONE;
-  }
-  // More operators remain.  A signal that arrived during the last operators of this call is
-  // honoured here: the device is already quiescent.
-  if (t->signal.load(std::memory_order_acquire)) {
-    finish(TaskState::Parked, true);
-    return FP_PREEMPTED;
-  }
-  finish(TaskState::Idle, false);
-  return FP_OK;
+  return static_cast<fp_status>(r);       // device errors: the backend has set the message
 }
 
 fp_status fp_preempt_signal(fp_prefill* t) {
   if (!t) return fail(FP_ERR_INVALID, "null task");
-  std::lock_guard<std::mutex> lk(t->mu);
-  switch (t->state) {
-    case TaskState::Running: t->signal.store(1, std::memory_order_release); return FP_OK;
-    case TaskState::Idle: t->state = TaskState::Parked; return FP_PREEMPTED;
-    case TaskState::Done: return FP_DONE;
-    case TaskState::Parked: return fail(FP_ERR_STATE, "task is already parked");
-  }
-  return FP_ERR_STATE;
+  const int r = t->core.preempt_signal();
+  if (r == fp::kTaskErrState) return fail(FP_ERR_STATE, "task is already parked");
+  return static_cast<fp_status>(r);
 }
 
 fp_status fp_preempt_wait(fp_prefill* t) {
   if (!t) return fail(FP_ERR_INVALID, "null task");
-  std::unique_lock<std::mutex> lk(t->mu);
-  for (;;) {
-    if (t->state == TaskState::Parked) return FP_PREEMPTED;
-    if (t->state == TaskState::Done) return FP_DONE;
-    if (t->state == TaskState::Idle) {
-      if (t->signal.load(std::memory_order_acquire)) {
-        t->signal.store(0, std::memory_order_release);
-        t->state = TaskState::Parked;
-        return FP_PREEMPTED;
-      }
-      return fail(FP_ERR_STATE, "no preemption pending on an idle task");
-    }
-    t->cv.wait(lk);
-  }
+  const int r = t->core.preempt_wait();
+  if (r == fp::kTaskErrState) return fail(FP_ERR_STATE, "no preemption pending on an idle task");
+  return static_cast<fp_status>(r);
 }
 
 fp_status fp_preempt(fp_prefill* t) {
@@ -678,16 +710,15 @@ fp_status fp_preempt(fp_prefill* t) {
 
 fp_status fp_resume(fp_prefill* t) {
   if (!t) return fail(FP_ERR_INVALID, "null task");
-  std::lock_guard<std::mutex> lk(t->mu);
-  if (t->state != TaskState::Parked) return fail(FP_ERR_STATE, "resume of a task that is not parked");
-  t->state = TaskState::Idle;
+  if (t->core.resume() != fp::kTaskOk) return fail(FP_ERR_STATE, "resume of a task that is not parked");
   return FP_OK;
 }
 
 fp_status fp_prefill_cursor(const fp_prefill* t, int32_t* layer, int32_t* op) {
   if (!t || !layer || !op) return fail(FP_ERR_INVALID, "null argument");
-  *layer = t->cursor / FP_OPS_PER_LAYER;
-  *op = t->cursor % FP_OPS_PER_LAYER;
+  const int32_t c = t->core.cursor();      // atomic: may be polled while another thread advances
+  *layer = c / FP_OPS_PER_LAYER;
+  *op = c % FP_OPS_PER_LAYER;
   return FP_OK;
 }
 
@@ -701,6 +732,19 @@ fp_status fp_prefill_block_tables(const fp_prefill* t, const int32_t** tables_ho
   if (!t || !tables_host || !max_blocks) return fail(FP_ERR_INVALID, "null argument");
   *tables_host = t->tables.data();
   *max_blocks = t->max_blocks;
+  return FP_OK;
+}
+
+fp_status fp_prefill_kv(const fp_prefill* t, int32_t layer, const void** k_pool, const void** v_pool,
+                        const int32_t** block_tables_host) {
+  if (!t || !k_pool || !v_pool || !block_tables_host) return fail(FP_ERR_INVALID, "null argument");
+  const fp_model* m = t->model;
+  if (layer < 0 || layer >= m->shape.n_layers) return fail(FP_ERR_INVALID, "layer out of range");
+  const size_t layer_bytes = (size_t)m->shape.kv_num_blocks * m->shape.n_kv_heads * fp::kKvBlock *
+                             m->shape.head_dim * m->elem;
+  *k_pool = static_cast<const char*>(m->k_pool) + (size_t)layer * layer_bytes;
+  *v_pool = static_cast<const char*>(m->v_pool) + (size_t)layer * layer_bytes;
+  *block_tables_host = t->tables.data();
   return FP_OK;
 }
 
@@ -738,8 +782,8 @@ void fp_prefill_end(fp_prefill* t) {
   (void)hipStreamSynchronize(m->stream);
   release_workspace(m, t->ws);
   if (!t->owned_blocks.empty()) (void)fp_kv_free(m, (int32_t)t->owned_blocks.size(), t->owned_blocks.data());
-  for (auto& ev : t->ring) if (ev) (void)hipEventDestroy(ev);
-  for (auto& ev : t->tev) if (ev) (void)hipEventDestroy(ev);
+  release_events(m, false, kMarkRing, t->ring);
+  release_events(m, true, (int)t->tev.size(), t->tev.data());
   {
     std::lock_guard<std::mutex> lk(m->mu);
     m->live_tasks--;
@@ -802,14 +846,28 @@ fp_status fp_diag_mfma_ceiling(int32_t milliseconds, void* hip_stream, double* t
   return st;
 }
 
-fp_status fp_op_gemm(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
-                     int64_t k, int32_t residual, void* hip_stream) {
+fp_status fp_op_gemm_ws(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
+                        int64_t k, int32_t residual, void* workspace, int64_t workspace_bytes,
+                        void* hip_stream) {
   if (!a || !w || !c || m <= 0 || n <= 0 || k <= 0 || (k % 8) || (n % 8) || m > INT32_MAX ||
       n > INT32_MAX || k > INT32_MAX || (dtype != 0 && dtype != 1))
     return fail(FP_ERR_INVALID, "fp_op_gemm: bad size, alignment or dtype");
-  fp::launch_gemm(dtype, a, w, c, m, n, k, residual, nullptr, 0, reinterpret_cast<hipStream_t>(hip_stream));
+  if (workspace_bytes < 0 || (workspace_bytes > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255))))
+    return fail(FP_ERR_INVALID, "fp_op_gemm_ws: workspace null, misaligned (256 bytes) or negative size");
+  fp::launch_gemm(dtype, a, w, c, m, n, k, residual, workspace, (size_t)workspace_bytes,
+                  reinterpret_cast<hipStream_t>(hip_stream));
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? FP_OK : fail(FP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(e));
+}
+
+fp_status fp_op_gemm(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
+                     int64_t k, int32_t residual, void* hip_stream) {
+  return fp_op_gemm_ws(dtype, a, w, c, m, n, k, residual, nullptr, 0, hip_stream);
+}
+
+int64_t fp_op_gemm_workspace_bytes(int32_t dtype, int64_t m, int64_t n, int64_t k) {
+  if (m <= 0 || n <= 0 || k <= 0) return 0;
+  return (int64_t)fp::gemm_workspace_bytes(dtype, m, n, k);
 }
 
 fp_status fp_op_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t m, int64_t f,

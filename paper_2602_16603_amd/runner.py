@@ -86,6 +86,7 @@ class PrefillTask:
         assert hidden.is_cuda and hidden.dtype == model.torch_dtype and hidden.is_contiguous()
         assert tuple(hidden.shape) == (self.cu[-1], model.spec.hidden)
         torch.cuda.current_stream().synchronize()   # hidden was produced on torch's stream
+        self._hidden_in = hidden                    # read asynchronously by the library: keep it alive
         self.handle = B.fp_prefill_begin(model.handle, hidden.data_ptr(), self.cu,
                                          None if cached is None else self.cached, block_tables,
                                          boundary_mask)
@@ -131,6 +132,10 @@ class PrefillTask:
         torch.cuda.synchronize()
         B.fp_prefill_moe_routing(self.handle, layer, ids.data_ptr(), wts.data_ptr())
         return ids, wts
+
+    def kv_pools(self, layer: int) -> Tuple[int, int, np.ndarray]:
+        """(device address of the layer's K pool slice, of its V pool slice, block tables)."""
+        return B.fp_prefill_kv(self.handle, layer, len(self.lengths))
 
     def block_tables(self) -> np.ndarray:
         return B.fp_prefill_block_tables(self.handle, len(self.lengths))

@@ -98,9 +98,10 @@ def _random_gemm_shapes(count, seed):
 
 @pytest.mark.parametrize("m,n,k,residual", _random_gemm_shapes(32, 20260216))
 def test_gemm_seeded_random_shapes(m, n, k, residual):
-    """Shapes drawn (seeded) across every dispatch of the bf16 GEMM -- the small-problem kernel,
-    split-K with its reduction, the 256x256-tile kernel -- with ragged rows, columns and K; rows
-    before and behind the output must stay untouched."""
+    """Shapes drawn (seeded) across the dispatches of the bf16 GEMM that need no workspace -- the
+    small-problem kernel and the 256x256-tile kernel -- with ragged rows, columns and K; rows
+    before and behind the output must stay untouched.  (The split-K form is reached through
+    fp_op_gemm_ws: test_gemm_split_k_with_workspace.)"""
     B = _binding()
     print(f"gemm random m={m} n={n} k={k} residual={residual}", flush=True)
     a = I.normal_tensor((m, k), 1.0, 31, torch.bfloat16, "cuda")
@@ -120,6 +121,49 @@ def test_gemm_seeded_random_shapes(m, n, k, residual):
         ref = ref + x0.cpu().double()
     assert max_rel_err(out, ref) <= TOL["bf16"]
     assert torch.all(buf[:g] == 7.0) and torch.all(buf[g + m:] == 7.0)
+
+
+@pytest.mark.parametrize("residual", [False, True])
+@pytest.mark.parametrize("m,n,k", [
+    (256, 6144, 4096), (1, 4096, 4096), (130, 4096, 14336), (1000, 4096, 4096), (1024, 6144, 4096),
+    (513, 4104, 1024), (300, 28672, 4096), (64, 5120, 27648), (777, 2056, 2048),
+])
+def test_gemm_split_k_with_workspace(residual, m, n, k):
+    """Short requests (the 128-1024-token prompts of the trace) leave too few output tiles to fill
+    the chip; with a workspace the GEMM is cut over K and a second kernel adds the partial sums in
+    a fixed order.  Ragged M and N, guard rows before and behind the output, the workspace's own
+    guard region untouched, the result against the definition and against the uncut form."""
+    B = _binding()
+    ws_bytes = B.fp_op_gemm_workspace_bytes(1, m, n, k)
+    print(f"gemm split-K m={m} n={n} k={k} residual={residual} workspace={ws_bytes}", flush=True)
+    assert ws_bytes > 0, "shape chosen for the split-K path does not split"
+    a = I.normal_tensor((m, k), 1.0, 35, torch.bfloat16, "cuda")
+    w = I.normal_tensor((n, k), 0.05, 36, torch.bfloat16, "cuda")
+    td = torch.float32 if residual else torch.bfloat16
+    g = 3
+    buf = torch.full((m + 2 * g, n), 7.0, dtype=td, device="cuda")
+    if residual:
+        buf[g:g + m] = I.normal_tensor((m, n), 1.0, 37, torch.float32, "cuda")
+    x0 = buf[g:g + m].clone()
+    plain = x0.clone()
+    out = buf[g:g + m]
+    pad = 4096
+    ws = torch.full((ws_bytes + pad,), 0x5A, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    B.fp_op_gemm_ws(1, a.data_ptr(), w.data_ptr(), out.data_ptr(), m, n, k, residual, ws.data_ptr(), ws_bytes)
+    B.fp_op_gemm(1, a.data_ptr(), w.data_ptr(), plain.data_ptr(), m, n, k, residual)
+    torch.cuda.synchronize()
+    ref = O.linear(a.cpu(), w.cpu())
+    if residual:
+        ref = ref + x0.cpu().double()
+    assert max_rel_err(out, ref) <= TOL["bf16"]
+    assert max_rel_err(out, plain.cpu().double()) <= 1e-2          # same sums, another fp32 order
+    assert torch.all(buf[:g] == 7.0) and torch.all(buf[g + m:] == 7.0)
+    assert torch.all(ws[ws_bytes:] == 0x5A)
+    again = x0.clone()                                              # fixed-order reduction: repeats bit for bit
+    B.fp_op_gemm_ws(1, a.data_ptr(), w.data_ptr(), again.data_ptr(), m, n, k, residual, ws.data_ptr(), ws_bytes)
+    torch.cuda.synchronize()
+    assert torch.equal(again, out)
 
 
 @pytest.mark.parametrize("name", ["bf16", "fp32"])

@@ -147,3 +147,112 @@ def test_state_errors():
         task.advance()                                  # done
     task.end()
     model.close()
+
+
+@pytest.mark.parametrize("ahead", [1, 2])
+def test_blocking_time_is_bounded_by_launch_ahead_operators(ahead):
+    """Section 5.1: with a check after every operator the wait for an acknowledgement is bounded by
+    the operators already handed to the device -- launch_ahead of them (the host enqueues operator
+    i only once operator i - launch_ahead has completed).  Signals raised at 16 different moments
+    of a 2-layer 8B-shaped prefill of 8192 tokens; signal -> acknowledgement (device drained) must
+    stay below launch_ahead x the slowest operator + 1 ms of host slack (thread wake-up, drain)."""
+    B, R = _mods()
+    spec = I.LLAMA3_8B.with_layers(2)
+    n = 8192
+    weights = I.make_weights(spec, 35, torch.bfloat16, "cuda")
+    model = R.PrefillModel(spec, weights, B.FP_DTYPE_BF16, n // 16 + 8, n)
+    hidden = I.make_hidden(n, spec.hidden, 35, torch.bfloat16, "cuda")
+    for _ in range(2):                                   # warm-up, then a timed run for the operator times
+        task = model.begin(hidden, [n])
+        B.fp_prefill_set_timing(task.handle, True)
+        task.run_to_completion()
+        op_ms = B.fp_prefill_op_times(task.handle, spec.n_layers * 9)
+        task.end()
+    slowest_ms, total_ms = max(op_ms), sum(op_ms)
+    bound_ms = ahead * slowest_ms + 1.0
+    worst, parked = 0.0, 0
+    for i in range(16):
+        delay_ms = total_ms * (i + 0.5) / 18.0           # spread over the run, always before its end
+        task = model.begin(hidden, [n])
+        B.fp_prefill_set_launch_ahead(task.handle, ahead)
+        th = threading.Thread(target=lambda t=task: t.advance())
+        th.start()
+        time.sleep(delay_ms / 1e3)
+        t0 = time.perf_counter()
+        st = B.fp_preempt_signal(task.handle)
+        if st == B.FP_OK:
+            st = B.fp_preempt_wait(task.handle)
+        blocked_ms = (time.perf_counter() - t0) * 1e3
+        th.join(30)
+        assert not th.is_alive()
+        if st == B.FP_PREEMPTED and task.cursor() != (0, 0):
+            parked += 1
+            worst = max(worst, blocked_ms)
+            assert blocked_ms <= bound_ms, (f"signal {delay_ms:.2f} ms into the run: blocked {blocked_ms:.3f} ms "
+                                            f"> {ahead} x {slowest_ms:.3f} ms + 1 ms")
+        task.end()
+    print(f"  launch_ahead {ahead}: {parked} preemptions, worst blocking {worst:.3f} ms, "
+          f"slowest operator {slowest_ms:.3f} ms, bound {bound_ms:.3f} ms", flush=True)
+    assert parked >= 8
+    model.close()
+
+
+def test_preserved_kv_state_is_addressable_through_the_block_tables():
+    """fp_prefill_kv hands out what a preempted task preserves of its KV cache (Section 4): the
+    layer's slice of the paged pools and the task's block tables.  Reading the pools through the
+    tables reproduces fp_prefill_kv_gather for every position, key head and channel (keys
+    [block][Hkv][16][D], values transposed inside the block [block][Hkv][D][16])."""
+    B, R = _mods()
+    spec = I.TINY
+    lengths = [70, 0, 33]
+    blocks = 24
+    weights = I.make_weights(spec, 36, torch.bfloat16, "cuda")
+    model = R.PrefillModel(spec, weights, B.FP_DTYPE_BF16, blocks, 128)
+    hidden = I.make_hidden(sum(lengths), spec.hidden, 36, torch.bfloat16, "cuda")
+    table, _ = I.permuted_block_tables(lengths, None, 16, blocks, seed=36)
+    task = model.begin(hidden, lengths, cached=[0, 0, 0], block_tables=table)
+    st, done = task.advance(9 + 3)                       # layer 0 complete, layer 1 through rope_kvwrite
+    assert st == B.FP_OK and done == 12
+    assert task.preempt() == B.FP_PREEMPTED
+    per_layer = blocks * spec.n_kv_heads * 16 * spec.head_dim
+    k_all, v_all = B.fp_model_kv_pools(model.handle)
+    for layer in range(spec.n_layers):
+        k_ptr, v_ptr, tables = task.kv_pools(layer)
+        assert k_ptr == k_all + layer * per_layer * 2 and v_ptr == v_all + layer * per_layer * 2
+        assert (tables == table).all()
+        kp = R.copy_from_device_ptr(k_ptr, (blocks, spec.n_kv_heads, 16, spec.head_dim), torch.bfloat16)
+        vp = R.copy_from_device_ptr(v_ptr, (blocks, spec.n_kv_heads, spec.head_dim, 16), torch.bfloat16)
+        for s, n in enumerate(lengths):
+            if n == 0:
+                continue
+            k_ref, v_ref = task.kv(layer, s)
+            pos = torch.arange(n)
+            blk = torch.as_tensor(tables[s], device="cuda").long()[pos // 16]
+            k_got = kp[blk, :, pos % 16, :]                        # [n, Hkv, D]
+            v_got = vp[blk, :, :, pos % 16]                        # [n, Hkv, D]
+            assert torch.equal(k_got, k_ref) and torch.equal(v_got, v_ref)
+    with pytest.raises(B.FlowPrefillError):
+        task.kv_pools(spec.n_layers)
+    task.resume()
+    task.run_to_completion()
+    task.end()
+    model.close()
+
+
+def test_model_destroy_is_refused_while_a_task_is_alive():
+    B, R = _mods()
+    spec = I.TINY
+    weights = I.make_weights(spec, 37, torch.bfloat16, "cuda")
+    model = R.PrefillModel(spec, weights, B.FP_DTYPE_BF16, 16, 64)
+    hidden = I.make_hidden(32, spec.hidden, 37, torch.bfloat16, "cuda")
+    task = model.begin(hidden, [32])
+    B.fp_model_destroy(model.handle)                      # refused: the task's buffers live in the model
+    assert "not ended" in B.fp_last_error()
+    task.run_to_completion()                              # the model is still whole
+    first = task.hidden()
+    task.end()
+    again = model.begin(hidden, [32])
+    again.run_to_completion()
+    assert torch.equal(again.hidden(), first)
+    again.end()
+    model.close()

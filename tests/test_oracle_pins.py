@@ -435,3 +435,30 @@ def test_moe_forcing_the_oracles_own_selection_changes_nothing():
     worse = ids.clone()
     worse[:, 1] = torch.tensor([[e for e in range(4) if e not in row.tolist()][0] for row in ids])   # swap in an unselected expert
     assert float(O.moe_selection_shortfall(h, wr, worse, 2).min()) > 0.0
+
+
+def test_moe_shortfall_and_weights_closed_form():
+    """A one-hot activation makes the router logits a column of W_r, so the probabilities, the
+    renormalised weights of any expert set and the shortfall of a set that misses the k-th
+    expert are all hand-computable: p = softmax(l); weights = p[ids] / sum p[ids]; shortfall =
+    p_(k) - min p[ids] (Section 7: the `gate` operator; reading: softmax over all experts, then
+    top-k, then renormalise)."""
+    import math
+    logits = [0.3, 2.0, -1.0, 1.5, 0.9, -0.2]                # experts sorted by p: 1, 3, 4, 0, 5, 2
+    h = torch.zeros((1, 4), dtype=torch.float64)
+    h[0, 2] = 1.0
+    wr = torch.zeros((6, 4), dtype=torch.float64)
+    wr[:, 2] = torch.tensor(logits, dtype=torch.float64)
+    z = sum(math.exp(v) for v in logits)
+    p = [math.exp(v) / z for v in logits]
+    ids, wts = O.moe_route(h, wr, 3)
+    assert ids.tolist() == [[1, 3, 4]]
+    s3 = p[1] + p[3] + p[4]
+    assert wts[0].tolist() == pytest.approx([p[1] / s3, p[3] / s3, p[4] / s3], rel=1e-14)
+    # expert 0 (4th) instead of expert 4 (3rd): not a top-3 set; the shortfall is p_(3) - p[0]
+    other = torch.tensor([[3, 0, 1]])
+    assert float(O.moe_selection_shortfall(h, wr, other, 3)[0]) == pytest.approx(p[4] - p[0], rel=1e-13)
+    so = p[3] + p[0] + p[1]
+    assert O.moe_weights_for(h, wr, other)[0].tolist() == pytest.approx([p[3] / so, p[0] / so, p[1] / so], rel=1e-14)
+    # any ordering of a true top-3 set has no shortfall
+    assert float(O.moe_selection_shortfall(h, wr, torch.tensor([[4, 1, 3]]), 3)[0]) == 0.0
