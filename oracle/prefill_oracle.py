@@ -225,15 +225,16 @@ def moe_weights_for(h: torch.Tensor, w_router: torch.Tensor, ids: torch.Tensor) 
 
 
 def moe_selection_shortfall(h: torch.Tensor, w_router: torch.Tensor, ids: torch.Tensor,
-                            top_k: int) -> torch.Tensor:
+                            top_k: int, relative: bool = False) -> torch.Tensor:
     """Per token: (the oracle's k-th largest router probability) - (the smallest probability among
-    the given experts), clipped at 0.  Zero when `ids` is a top-k set of the oracle's
-    probabilities; a value of the order of the implementation's rounding error means the
-    implementation resolved a near-tie the other way."""
+    the given experts), clipped at 0; with `relative`, divided by that k-th largest probability.
+    Zero when `ids` is a top-k set of the oracle's probabilities; a value of the order of the
+    implementation's rounding error means the implementation resolved a near-tie the other way."""
     prob = torch.softmax(linear(h, w_router), dim=-1)
     kth = torch.sort(prob, dim=-1, descending=True).values[:, top_k - 1]
     weakest = torch.gather(prob, 1, ids.to(torch.int64).cpu()).min(dim=-1).values
-    return torch.clamp(kth - weakest, min=0.0)
+    gap = torch.clamp(kth - weakest, min=0.0)
+    return gap / kth if relative else gap
 
 
 def moe_mlp(h: torch.Tensor, w_router: torch.Tensor, w_gate_up: torch.Tensor, w_down: torch.Tensor,
@@ -322,6 +323,7 @@ def layer_forward(shape: Shape, w: LayerWeights, x: torch.Tensor, cu_seqlens: Se
     if w.w_router is not None:
         if forced_ids is not None and shortfall_out is not None:
             shortfall_out.append(moe_selection_shortfall(h2, w.w_router, forced_ids, shape.top_k))
+            shortfall_out.append(moe_selection_shortfall(h2, w.w_router, forced_ids, shape.top_k, relative=True))
         x = x + moe_mlp(h2, w.w_router, w.w_gate_up, w.w_down, shape.top_k, forced_ids, weights_out)
     else:
         act = silu_mul(linear(h2, w.w_gate_up))

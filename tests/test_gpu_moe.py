@@ -40,17 +40,27 @@ def run_and_check(spec, lengths, seed, pool_blocks):
     shortfall, ref_wts = [], []
     x_ref, cache_ref = O.prefill(oracle_shape(spec), oracle_layers(weights), hidden, I.cu_seqlens_of(lengths),
                                  forced_ids=forced, shortfall_out=shortfall, weights_out=ref_wts)
-    worst = max(float(s.max()) for s in shortfall) if total else 0.0
-    flipped = sum(int((s > 0).sum()) for s in shortfall) / max(1, total * spec.n_layers)
+    absolute, relative = shortfall[0::2], shortfall[1::2]      # per layer: absolute, then relative to the k-th probability
+    worst = max(float(s.max()) for s in absolute) if total else 0.0
+    worst_rel = max(float(s.max()) for s in relative) if total else 0.0
+    flipped = sum(int((s > 0).sum()) for s in absolute) / max(1, total * spec.n_layers)
     e = max_rel_err(got, x_ref)
     # The GPU's renormalised weights against the oracle's own probabilities of the same experts,
     # element by element (fp32 softmax of bf16 activations against fp64 of fp64 activations).
     w_err = max((float((g.double() - r).abs().max()) for g, r in zip(gpu_wts, ref_wts)), default=0.0) if total else 0.0
     w_fro = max((fro_rel_err(g, r) for g, r in zip(gpu_wts, ref_wts)), default=0.0) if total else 0.0
-    print(f"  hidden: E={e:.3e} fro={fro_rel_err(got, x_ref):.3e}; router: worst shortfall {worst:.2e}, "
+    print(f"  hidden: E={e:.3e} fro={fro_rel_err(got, x_ref):.3e}; router: worst shortfall {worst:.2e} "
+          f"({worst_rel:.2e} of the k-th probability), "
           f"{100 * flipped:.2f}% of token-layers decided the other way; weights: max abs err {w_err:.2e}, "
           f"fro {w_fro:.2e}", flush=True)
-    assert worst <= 5e-4 and flipped <= 0.02      # only near-ties differ
+    # Only near-ties may differ.  The GPU's router reads the bf16-stored activations (2^-9 relative
+    # rounding per element, on top of the layer's accumulated bf16 error), which moves a logit by
+    # about 0.2 * sqrt(hidden) * 2^-9 / sqrt(3): 0.004 (hidden 256) to 0.01 (hidden 2048) standard
+    # deviations, and the difference of two logits by sqrt(2) of that.  Two experts can change
+    # places when their probabilities are within about four such deviations of each other: a
+    # relative gap of 6e-2 at the largest shape tested.  Observed: 4.1e-2 there (6.3e-5 absolute:
+    # the 8th of 128 probabilities is small), 0.6 % at the 8-expert shape (6.1e-4 absolute).
+    assert worst <= 1e-3 and worst_rel <= 6e-2 and flipped <= 0.02
     assert w_err <= 3e-2 and w_fro <= 1e-2
     assert e <= TOL["bf16"]
     for layer in range(spec.n_layers):

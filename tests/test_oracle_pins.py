@@ -458,6 +458,7 @@ def test_moe_shortfall_and_weights_closed_form():
     # expert 0 (4th) instead of expert 4 (3rd): not a top-3 set; the shortfall is p_(3) - p[0]
     other = torch.tensor([[3, 0, 1]])
     assert float(O.moe_selection_shortfall(h, wr, other, 3)[0]) == pytest.approx(p[4] - p[0], rel=1e-13)
+    assert float(O.moe_selection_shortfall(h, wr, other, 3, relative=True)[0]) == pytest.approx(1.0 - p[0] / p[4], rel=1e-12)
     so = p[3] + p[0] + p[1]
     assert O.moe_weights_for(h, wr, other)[0].tolist() == pytest.approx([p[3] / so, p[0] / so, p[1] / so], rel=1e-14)
     # any ordering of a true top-3 set has no shortfall
