@@ -258,6 +258,22 @@ fp_status fp_op_gemm_ws(int32_t dtype, const void* a, const void* w, void* c, in
                         int64_t k, int32_t residual, void* workspace /*device*/,
                         int64_t workspace_bytes, void* hip_stream);
 int64_t fp_op_gemm_workspace_bytes(int32_t dtype, int64_t m, int64_t n, int64_t k);
+
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): fp_op_gemm_ws without a workspace argument.  The split-K partial sums go
+ * to a static device array of FP_NOALLOC_SCRATCH_BYTES inside the library (each GPU the library
+ * runs on holds its own copy until the process ends); the call allocates and frees nothing --
+ * no hipMalloc, no hipFree, no allocating library routine.  Same kernels and the same bits as
+ * fp_op_gemm_ws given fp_op_gemm_workspace_bytes of workspace.  The first call on a device looks
+ * the array's address up once (hipGetSymbolAddress); make that call outside a capture.
+ * FP_ERR_INVALID, with nothing launched, when the problem wants more scratch than the array holds
+ * (fp_op_gemm_workspace_bytes(...) > FP_NOALLOC_SCRATCH_BYTES) or on the size errors of fp_op_gemm.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams or threads) race on it; the array keeps the previous call's contents between calls and
+ * none of it needs to start at zero.                                                              */
+#define FP_NOALLOC_SCRATCH_BYTES (32 * 1024 * 1024)
+fp_status fp_op_gemm_noalloc(int32_t dtype, const void* a, const void* w, void* c, int64_t m,
+                             int64_t n, int64_t k, int32_t residual, void* hip_stream);
 fp_status fp_op_rmsnorm(int32_t dtype, const void* x_f32, const void* gain, void* out,
                         int64_t t, int64_t d, float eps, void* hip_stream);
 fp_status fp_op_silu_mul(int32_t dtype, const void* gu, void* out, int64_t t, int64_t f,

@@ -71,6 +71,7 @@ _SIGS = {
     "fp_prefill_end": (None, [_P]),
     "fp_op_gemm": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _P]),
     "fp_op_gemm_ws": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _P, C.c_int64, _P]),
+    "fp_op_gemm_noalloc": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _P]),
     "fp_op_gemm_workspace_bytes": (C.c_int64, [C.c_int32, C.c_int64, C.c_int64, C.c_int64]),
     "fp_op_rmsnorm": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_float, _P]),
     "fp_op_silu_mul": (C.c_int, [C.c_int32, _P, _P, C.c_int64, C.c_int64, _P]),
@@ -259,6 +260,15 @@ def fp_op_gemm_ws(dtype: int, a: int, w: int, c: int, m: int, n: int, k: int, re
                   workspace: int, workspace_bytes: int, hip_stream: int = 0) -> None:
     _check(lib.fp_op_gemm_ws(dtype, _P(a), _P(w), _P(c), m, n, k, 1 if residual else 0, _P(workspace),
                              workspace_bytes, _P(hip_stream)), "fp_op_gemm_ws")
+
+
+FP_NOALLOC_SCRATCH_BYTES = 32 * 1024 * 1024
+
+
+def fp_op_gemm_noalloc(dtype: int, a: int, w: int, c: int, m: int, n: int, k: int, residual: bool,
+                       hip_stream: int = 0) -> None:
+    _check(lib.fp_op_gemm_noalloc(dtype, _P(a), _P(w), _P(c), m, n, k, 1 if residual else 0, _P(hip_stream)),
+           "fp_op_gemm_noalloc")
 
 
 def fp_op_gemm_workspace_bytes(dtype: int, m: int, n: int, k: int) -> int:

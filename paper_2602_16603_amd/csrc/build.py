@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 PKG = os.path.dirname(HERE)
 LIB = os.path.join(PKG, "libflowprefill.so")
-SOURCES = ["runtime.hip", "gemm.hip", "attention.hip", "elementwise.hip", "scheduler.hip", "moe.hip"]
+SOURCES = ["runtime.hip", "gemm.hip", "attention.hip", "elementwise.hip", "scheduler.hip", "moe.hip", "noalloc.hip"]
 # attention.hip never produces a NaN (masked scores are -inf and only ever meet finite values),
 # so the max reductions need no NaN-quieting canonicalisation.
 EXTRA = {"attention.hip": ["-fno-honor-nans"]}
