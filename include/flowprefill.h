@@ -259,6 +259,23 @@ fp_status fp_op_gemm_ws(int32_t dtype, const void* a, const void* w, void* c, in
                         int64_t workspace_bytes, void* hip_stream);
 int64_t fp_op_gemm_workspace_bytes(int32_t dtype, int64_t m, int64_t n, int64_t k);
 
+/* The short-request form of two operator pairs of the layer (the operators between the core
+ * operators of Section 5.1; requests of 128-1024 tokens, Section 6.1): when a projection is cut
+ * over K, the kernel that adds the partial sums also carries out the operator that follows, so
+ * that operator launches nothing (its cursor position and boundary remain).  bf16 only.
+ *   FP_TAIL_RMSNORM  residual = 1: c (fp32 [M,N]) += A W^T, then tail_out [M,N] (bf16) =
+ *                    rmsnorm(updated row of c, eps) * gain[N]           (o_proj / down_proj + RMSNorm)
+ *   FP_TAIL_SWIGLU   residual = 0, N = 2F, gate columns first: tail_out [M,F] (bf16) =
+ *                    silu(bf16(gate)) * bf16(up); c is not written and may be NULL  (gate_up_proj + SiLU*up)
+ * Same bits as fp_op_gemm_ws followed by fp_op_rmsnorm / fp_op_silu_mul.  FP_ERR_INVALID, with
+ * nothing launched, when the problem would not be cut over K with this workspace (see
+ * fp_op_gemm_workspace_bytes), N > 8192 for FP_TAIL_RMSNORM, or on the size errors of fp_op_gemm.   */
+enum { FP_TAIL_RMSNORM = 1, FP_TAIL_SWIGLU = 2 };
+fp_status fp_op_gemm_tail(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
+                          int64_t k, int32_t residual, void* workspace /*device*/, int64_t workspace_bytes,
+                          int32_t tail, const void* gain /*device, FP_TAIL_RMSNORM*/,
+                          void* tail_out /*device*/, float eps, void* hip_stream);
+
 /* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc): fp_op_gemm_ws without a workspace argument.  The split-K partial sums go
  * to a static device array of FP_NOALLOC_SCRATCH_BYTES inside the library (each GPU the library

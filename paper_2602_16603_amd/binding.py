@@ -71,6 +71,8 @@ _SIGS = {
     "fp_prefill_end": (None, [_P]),
     "fp_op_gemm": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _P]),
     "fp_op_gemm_ws": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _P, C.c_int64, _P]),
+    "fp_op_gemm_tail": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _P, C.c_int64,
+                                  C.c_int32, _P, _P, C.c_float, _P]),
     "fp_op_gemm_noalloc": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _P]),
     "fp_op_gemm_workspace_bytes": (C.c_int64, [C.c_int32, C.c_int64, C.c_int64, C.c_int64]),
     "fp_op_rmsnorm": (C.c_int, [C.c_int32, _P, _P, _P, C.c_int64, C.c_int64, C.c_float, _P]),
@@ -260,6 +262,17 @@ def fp_op_gemm_ws(dtype: int, a: int, w: int, c: int, m: int, n: int, k: int, re
                   workspace: int, workspace_bytes: int, hip_stream: int = 0) -> None:
     _check(lib.fp_op_gemm_ws(dtype, _P(a), _P(w), _P(c), m, n, k, 1 if residual else 0, _P(workspace),
                              workspace_bytes, _P(hip_stream)), "fp_op_gemm_ws")
+
+
+FP_TAIL_RMSNORM, FP_TAIL_SWIGLU = 1, 2
+
+
+def fp_op_gemm_tail(a: int, w: int, c: int, m: int, n: int, k: int, residual: bool, workspace: int,
+                    workspace_bytes: int, tail: int, gain: int, tail_out: int, eps: float = 0.0,
+                    hip_stream: int = 0) -> None:
+    _check(lib.fp_op_gemm_tail(FP_DTYPE_BF16, _P(a), _P(w), _P(c), m, n, k, 1 if residual else 0, _P(workspace),
+                               workspace_bytes, tail, _P(gain), _P(tail_out), C.c_float(eps), _P(hip_stream)),
+           "fp_op_gemm_tail")
 
 
 FP_NOALLOC_SCRATCH_BYTES = 32 * 1024 * 1024

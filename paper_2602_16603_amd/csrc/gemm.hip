@@ -614,6 +614,96 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   }
 }
 
+// Split-K reduction of a gate_up projection fused with SiLU(gate)*up: part [splits][M][2F] fp32
+// -> out [M][F].  Gate and up sums are rounded to bf16 first, so the result has the bits of
+// splitk_reduce_kernel<false> into [M][2F] followed by the stand-alone silu_mul operator, without
+// that intermediate.  One thread per 8 outputs.
+__global__ __launch_bounds__(256) void splitk_reduce_swiglu_kernel(const float* __restrict__ part,
+                                                                   bf16* __restrict__ out, int64_t m,
+                                                                   int64_t f, int splits) {
+  const int64_t f8 = f / 8;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= m * f8) return;
+  const int64_t r = i / f8, c = i - r * f8;
+  const int64_t mn = m * 2 * f;
+  const float* row = part + r * 2 * f + c * 8;
+  f32x8 g = Vec8<float>::load(row), u = Vec8<float>::load(row + f);
+  for (int z = 1; z < splits; ++z) {
+    const f32x8 gz = Vec8<float>::load(row + z * mn), uz = Vec8<float>::load(row + z * mn + f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { g[e] += gz[e]; u[e] += uz[e]; }
+  }
+  f32x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+    o[e] = silu_mul_f32(static_cast<float>(static_cast<bf16>(g[e])), static_cast<float>(static_cast<bf16>(u[e])));
+  Vec8<bf16>::store(out + r * f + c * 8, o);
+}
+
+// Split-K reduction of a residual projection fused with the RMSNorm that follows it: one
+// 256-thread workgroup per token row adds the partial sums (in index order) and the residual,
+// writes the new residual row, and normalises it from registers into h -- the arithmetic, in the
+// order, of splitk_reduce_kernel<true> followed by the stand-alone RMSNorm operator, which then
+// has nothing left to do.  Rows of up to kTailNormCols columns.
+constexpr int kTailNormVec = 4;
+constexpr int kTailNormCols = 256 * 8 * kTailNormVec;
+__global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(const float* __restrict__ part,
+                                                                 float* __restrict__ x,
+                                                                 const bf16* __restrict__ gain,
+                                                                 bf16* __restrict__ h, int64_t mn, int n,
+                                                                 int splits, float eps) {
+  __shared__ float partial[4];
+  const int tid = threadIdx.x;
+  const int64_t at = (int64_t)blockIdx.x * n;
+  const int n8 = n / 8;
+  f32x8 held[kTailNormVec];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < kTailNormVec; ++i) {
+    const int c = tid + i * 256;
+    if (c < n8) {
+      const f32x8 xv = Vec8<float>::load(x + at + c * 8);
+      f32x8 acc = Vec8<float>::load(part + at + c * 8);
+      int z = 1;
+      for (; z + 3 < splits; z += 4) {               // four loads in flight; added in index order
+        const f32x8 v0 = Vec8<float>::load(part + z * mn + at + c * 8);
+        const f32x8 v1 = Vec8<float>::load(part + (z + 1) * mn + at + c * 8);
+        const f32x8 v2 = Vec8<float>::load(part + (z + 2) * mn + at + c * 8);
+        const f32x8 v3 = Vec8<float>::load(part + (z + 3) * mn + at + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = ((acc[e] + v0[e]) + v1[e]) + v2[e] + v3[e];
+      }
+      for (; z < splits; ++z) {
+        const f32x8 v = Vec8<float>::load(part + z * mn + at + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += v[e];
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += xv[e];
+      Vec8<float>::store(x + at + c * 8, acc);
+      held[i] = acc;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += acc[e] * acc[e];
+    }
+  }
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) partial[tid >> 6] = ss;
+  __syncthreads();
+  const float total = partial[0] + partial[1] + partial[2] + partial[3];
+  const float inv = 1.0f / sqrtf(total / (float)n + eps);
+#pragma unroll
+  for (int i = 0; i < kTailNormVec; ++i) {
+    const int c = tid + i * 256;
+    if (c < n8) {
+      const f32x8 g = Vec8<bf16>::load(gain + c * 8);
+      f32x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = held[i][e] * inv * g[e];
+      Vec8<bf16>::store(h + at + c * 8, o);
+    }
+  }
+}
+
 // How many K ranges to cut a problem into so that a launch has about one workgroup per CU:
 // only when the 256x256 tiles alone leave most of the chip idle, and never below 8 k-tiles
 // (512 columns) per range.  1 = no split.
@@ -658,9 +748,10 @@ size_t gemm_workspace_bytes(int dtype, int64_t m, int64_t n, int64_t k) {
   return s > 1 ? (size_t)s * m * n * sizeof(float) : 0;
 }
 
+// tail: what follows the split-K reduction in the same kernel (kTailNone: nothing).
 template <bool RESID>
 static void launch_bf16_w4(const bf16* a, const bf16* w, void* c, int m, int n, int k, int splits,
-                           float* workspace, hipStream_t s) {
+                           float* workspace, const GemmTail& tail, hipStream_t s) {
   const int tiles_m = (m + 255) / 256, tiles_n = (n + 255) / 256;
   const int kt = k / kBK;
   if (splits <= 1) {
@@ -673,8 +764,15 @@ static void launch_bf16_w4(const bf16* a, const bf16* w, void* c, int m, int n, 
   gemm_bf16_w4_kernel<kEpiPartial><<<dim3((unsigned)(tiles_m * tiles_n * used)), 256, 0, s>>>(
       a, w, workspace, m, n, k, tiles_m, tiles_n, per, nullptr);
   const int64_t mn = (int64_t)m * n;
-  splitk_reduce_kernel<RESID><<<dim3((unsigned)((mn / 8 + 255) / 256)), 256, 0, s>>>(workspace, c, mn / 8,
-                                                                                   mn, used);
+  if (RESID && tail.kind == kTailRmsNorm)
+    splitk_reduce_norm_kernel<<<dim3((unsigned)m), 256, 0, s>>>(workspace, (float*)c, (const bf16*)tail.gain,
+                                                               (bf16*)tail.out, mn, n, used, tail.eps);
+  else if (!RESID && tail.kind == kTailSwiGLU)
+    splitk_reduce_swiglu_kernel<<<dim3((unsigned)(((int64_t)m * (n / 2) / 8 + 255) / 256)), 256, 0, s>>>(
+        workspace, (bf16*)tail.out, m, n / 2, used);
+  else
+    splitk_reduce_kernel<RESID><<<dim3((unsigned)((mn / 8 + 255) / 256)), 256, 0, s>>>(workspace, c, mn / 8,
+                                                                                     mn, used);
 }
 
 template <int BM, int BN, int WGM, int WGN, bool RESID>
@@ -742,8 +840,27 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
     }
 }
 
+// Number of K ranges launch_gemm cuts the problem into with that much workspace (1 = uncut; 0 = the
+// problem does not run on the fast kernel at all).
+static int w4_plan(int dtype, int64_t m, int64_t n, int64_t k, size_t workspace_bytes) {
+  if (dtype != 1 || k % kBK != 0 || n % 8 != 0 || n > (1 << 21) || k > (1 << 21)) return 0;
+  // (the size limits keep the fast kernel's 32-bit buffer offsets below kOffOutOfRange)
+  const int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
+  int splits = w4_splits(m, n, k);
+  if (splits > 1 && (size_t)splits * m * n * sizeof(float) > workspace_bytes) splits = 1;
+  return big_tiles * splits >= 96 ? splits : 0;
+}
+
+bool gemm_tail_fusable(int dtype, int64_t m, int64_t n, int64_t k, size_t workspace_bytes, int tail_kind) {
+  if (w4_plan(dtype, m, n, k, workspace_bytes) <= 1) return false;      // tails ride on the split-K reduction
+  if (tail_kind == kTailRmsNorm) return n <= kTailNormCols;
+  if (tail_kind == kTailSwiGLU) return n % 16 == 0;
+  return false;
+}
+
 void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
-                 int64_t k, int residual, void* workspace, size_t workspace_bytes, hipStream_t s) {
+                 int64_t k, int residual, void* workspace, size_t workspace_bytes, hipStream_t s,
+                 const GemmTail* tail) {
   if (m == 0 || n == 0) return;
   if (dtype == 0) {
     dim3 grid((unsigned)((n + 63) / 64), (unsigned)((m + 63) / 64));
@@ -760,13 +877,12 @@ void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, in
   // K a multiple of 64 and enough 256x256 tiles (or enough K to split) to occupy the chip: the
   // one-wave-per-SIMD DMA kernel, split over K when the caller's workspace allows.  Otherwise (tiny or
   // odd-K problems): the register-staged kernel on 128x128 tiles.
-  const int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
-  int splits = k % kBK == 0 ? w4_splits(m, n, k) : 1;
-  if (splits > 1 && (size_t)splits * m * n * sizeof(float) > workspace_bytes) splits = 1;
-  // (the size limits keep the fast kernel's 32-bit buffer offsets below kOffOutOfRange)
-  if (k % kBK == 0 && n % 8 == 0 && n <= (1 << 21) && k <= (1 << 21) && big_tiles * splits >= 96) {
-    if (residual) launch_bf16_w4<true>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, s);
-    else launch_bf16_w4<false>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, s);
+  const int splits = w4_plan(dtype, m, n, k, workspace_bytes);
+  const GemmTail none{};
+  const GemmTail& tl = tail && gemm_tail_fusable(dtype, m, n, k, workspace_bytes, tail->kind) ? *tail : none;
+  if (splits >= 1) {
+    if (residual) launch_bf16_w4<true>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, tl, s);
+    else launch_bf16_w4<false>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, tl, s);
   } else {
     if (residual) launch_bf16_cfg<128, 128, 2, 2, true>(pa, pw, c, (int)m, (int)n, (int)k, s);
     else launch_bf16_cfg<128, 128, 2, 2, false>(pa, pw, c, (int)m, (int)n, (int)k, s);

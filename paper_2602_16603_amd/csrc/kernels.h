@@ -47,8 +47,24 @@ void launch_attention(int dtype, const void* qkv, const void* k_pool, const void
 // `workspace` (device, may be null) holds split-K partial sums for problems too small to fill the
 // chip with output tiles alone; gemm_workspace_bytes says how much such a problem wants (0 if
 // it would not split).  Without enough workspace the problem runs unsplit.
+// `tail` (may be null): the operator that follows the projection, carried out by the split-K
+// reduction kernel when -- and only when -- gemm_tail_fusable says so for the same arguments
+// (short requests: one launch and one pass over the data fewer):
+//   kTailRmsNorm  residual projections: tail.out [M,N] (storage dtype) = rmsnorm(updated C row) * tail.gain
+//   kTailSwiGLU   gate_up projection (N = 2F, gate columns first): tail.out [M,F] = silu(gate) * up and C
+//                 is NOT written
+// with the bits the stand-alone operators give.
+enum { kTailNone = 0, kTailRmsNorm = 1, kTailSwiGLU = 2 };
+struct GemmTail {
+  int kind = kTailNone;
+  const void* gain = nullptr;
+  void* out = nullptr;
+  float eps = 0.f;
+};
+bool gemm_tail_fusable(int dtype, int64_t m, int64_t n, int64_t k, size_t workspace_bytes, int tail_kind);
 void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
-                 int64_t k, int residual, void* workspace, size_t workspace_bytes, hipStream_t s);
+                 int64_t k, int residual, void* workspace, size_t workspace_bytes, hipStream_t s,
+                 const GemmTail* tail = nullptr);
 size_t gemm_workspace_bytes(int dtype, int64_t m, int64_t n, int64_t k);
 // Fused gate_up projection + SiLU(gate)*up (bf16): out[m][f] from a[m][k] and w_gate_up[2f][k]
 // (gate rows first), bit-identical to launch_gemm into [m][2f] followed by launch_silu_mul.

@@ -103,7 +103,10 @@ struct fp_prefill : fp::OpBackend {
   int32_t *moe_ids = nullptr, *moe_slot = nullptr, *moe_plan = nullptr, *moe_groups = nullptr, *moe_blocks = nullptr;
   void *moe_hp = nullptr, *moe_act = nullptr, *moe_y = nullptr;
   int32_t moe_max_row_tiles = 0;
-  bool swiglu_fused = false;   // op 6 writes act directly (fused epilogue); op 7 then has no work and gu is not allocated
+  bool swiglu_fused = false;   // op 6 writes act directly (fused GEMM epilogue, or fused split-K reduction); op 7 then has no work and gu is not allocated
+  bool swiglu_epilogue = false;   // ... by the GEMM epilogue (the problem fills the chip); else by the split-K reduction
+  bool norm_after_o = false;   // short requests: op 4's split-K reduction also normalises the row (op 5 has no work)
+  bool norm_after_down = false;   // ... op 8's does (op 0 of the next layer has no work)
   void* splitk = nullptr;              // split-K partial sums (0 bytes when no GEMM of this task splits)
   size_t splitk_bytes = 0;
   fp::BatchMeta meta{};
@@ -165,7 +168,9 @@ fp_status launch_op(fp_prefill* t, int32_t index) {
     return FP_OK;
   }
   switch (op) {
-    case 0: fp::launch_rmsnorm(dt, t->x, w.attn_norm, t->h, T, d, sh.rms_eps, s); break;
+    case 0:
+      if (!(layer > 0 && t->norm_after_down)) fp::launch_rmsnorm(dt, t->x, w.attn_norm, t->h, T, d, sh.rms_eps, s);
+      break;
     case 1: fp::launch_gemm(dt, t->h, w.w_qkv, t->qkv, T, m->geo.qkv_width(), d, 0, t->splitk, t->splitk_bytes, s); break;
     case 2:
       fp::launch_rope_kvwrite(dt, t->qkv, m->rope_cos, m->rope_sin, m->geo, t->meta, layer,
@@ -174,16 +179,34 @@ fp_status launch_op(fp_prefill* t, int32_t index) {
     case 3:
       fp::launch_attention(dt, t->qkv, m->k_pool, m->v_pool, t->o, m->geo, t->meta, layer, s);
       break;
-    case 4: fp::launch_gemm(dt, t->o, w.w_o, t->x, T, d, qd, 1, t->splitk, t->splitk_bytes, s); break;
-    case 5: fp::launch_rmsnorm(dt, t->x, w.mlp_norm, t->h, T, d, sh.rms_eps, s); break;
+    case 4: {
+      fp::GemmTail tail;
+      if (t->norm_after_o) tail = fp::GemmTail{fp::kTailRmsNorm, w.mlp_norm, t->h, sh.rms_eps};
+      fp::launch_gemm(dt, t->o, w.w_o, t->x, T, d, qd, 1, t->splitk, t->splitk_bytes, s, &tail);
+      break;
+    }
+    case 5:
+      if (!t->norm_after_o) fp::launch_rmsnorm(dt, t->x, w.mlp_norm, t->h, T, d, sh.rms_eps, s);
+      break;
     case 6:
-      if (t->swiglu_fused) fp::launch_gemm_swiglu(t->h, w.w_gate_up, t->act, T, F, d, s);
-      else fp::launch_gemm(dt, t->h, w.w_gate_up, t->gu, T, 2 * F, d, 0, t->splitk, t->splitk_bytes, s);
+      if (t->swiglu_epilogue) {
+        fp::launch_gemm_swiglu(t->h, w.w_gate_up, t->act, T, F, d, s);
+      } else {
+        fp::GemmTail tail;
+        if (t->swiglu_fused) tail = fp::GemmTail{fp::kTailSwiGLU, nullptr, t->act, 0.f};
+        fp::launch_gemm(dt, t->h, w.w_gate_up, t->gu, T, 2 * F, d, 0, t->splitk, t->splitk_bytes, s, &tail);
+      }
       break;
     case 7:
       if (!t->swiglu_fused) fp::launch_silu_mul(dt, t->gu, t->act, T, F, s);
       break;
-    case 8: fp::launch_gemm(dt, t->act, w.w_down, t->x, T, d, F, 1, t->splitk, t->splitk_bytes, s); break;
+    case 8: {
+      fp::GemmTail tail;
+      if (t->norm_after_down && layer + 1 < sh.n_layers)
+        tail = fp::GemmTail{fp::kTailRmsNorm, m->layers[layer + 1].attn_norm, t->h, sh.rms_eps};
+      fp::launch_gemm(dt, t->act, w.w_down, t->x, T, d, F, 1, t->splitk, t->splitk_bytes, s, &tail);
+      break;
+    }
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess)
@@ -288,7 +311,9 @@ void fp_prefill::begin_call() {
 }
 
 int fp_prefill::launch(int32_t index, bool* launched) {
-  *launched = !(swiglu_fused && index % FP_OPS_PER_LAYER == 7);
+  const int op = index % FP_OPS_PER_LAYER;
+  *launched = !((swiglu_fused && op == 7) || (norm_after_o && op == 5) ||
+                (norm_after_down && op == 0 && index >= FP_OPS_PER_LAYER));
   return launch_op(this, index) == FP_OK ? 0 : -1;
 }
 
@@ -575,7 +600,17 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   auto carve = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
   const bool moe = sh.n_experts > 0;
   const size_t E = (size_t)sh.n_experts, pairs = Tn * (size_t)sh.top_k;
-  t->swiglu_fused = !moe && fp::gemm_swiglu_fusable(sh.dtype, T, (int64_t)F, (int64_t)d);
+  // Split-K workspace first: which operators fuse depends on whether their GEMM will be cut.
+  const size_t sk_dense = std::max(fp::gemm_workspace_bytes(sh.dtype, T, 2 * (int64_t)F, (int64_t)d),
+                                   fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)d, (int64_t)F));
+  const size_t sk_bytes = std::max(
+      std::max(fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)W, (int64_t)d), fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)d, (int64_t)qd)),
+      moe ? fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)E, (int64_t)d) : sk_dense);
+  t->swiglu_epilogue = !moe && fp::gemm_swiglu_fusable(sh.dtype, T, (int64_t)F, (int64_t)d);
+  t->swiglu_fused = t->swiglu_epilogue ||
+                    (!moe && fp::gemm_tail_fusable(sh.dtype, T, 2 * (int64_t)F, (int64_t)d, sk_bytes, fp::kTailSwiGLU));
+  t->norm_after_o = fp::gemm_tail_fusable(sh.dtype, T, (int64_t)d, (int64_t)qd, sk_bytes, fp::kTailRmsNorm);
+  t->norm_after_down = !moe && fp::gemm_tail_fusable(sh.dtype, T, (int64_t)d, (int64_t)F, sk_bytes, fp::kTailRmsNorm);
   const size_t o_x = carve(Tn * d * 4), o_h = carve(Tn * d * e), o_qkv = carve(Tn * W * e),
                o_o = carve(Tn * qd * e), o_gu = carve(t->swiglu_fused || moe ? 0 : Tn * 2 * F * e),
                o_act = carve(moe ? 0 : Tn * F * e);
@@ -586,11 +621,6 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
                o_mp = carve(moe ? E * 4 : 0), o_mb = carve(moe ? (size_t)fp::moe_route_blocks(T) * E * 4 : 0), o_mg = carve(moe ? (1 + 3 * (size_t)t->moe_max_row_tiles) * 4 : 0),
                o_mh = carve(moe ? pairs * d * e : 0), o_ma = carve(moe ? pairs * F * e : 0),
                o_my = carve(moe ? pairs * d * e : 0);
-  const size_t sk_dense = std::max(fp::gemm_workspace_bytes(sh.dtype, T, 2 * (int64_t)F, (int64_t)d),
-                                   fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)d, (int64_t)F));
-  const size_t sk_bytes = std::max(
-      std::max(fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)W, (int64_t)d), fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)d, (int64_t)qd)),
-      moe ? fp::gemm_workspace_bytes(sh.dtype, T, (int64_t)E, (int64_t)d) : sk_dense);
   const size_t o_sk = carve(sk_bytes);
   const size_t n_int = tok_seq.size() + tok_pos.size() + t->cu.size() + t->cached.size() +
                        t->tables.size() + kv_items.size() + attn_items.size();
@@ -863,6 +893,28 @@ fp_status fp_op_gemm_ws(int32_t dtype, const void* a, const void* w, void* c, in
 fp_status fp_op_gemm(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
                      int64_t k, int32_t residual, void* hip_stream) {
   return fp_op_gemm_ws(dtype, a, w, c, m, n, k, residual, nullptr, 0, hip_stream);
+}
+
+fp_status fp_op_gemm_tail(int32_t dtype, const void* a, const void* w, void* c, int64_t m, int64_t n,
+                          int64_t k, int32_t residual, void* workspace, int64_t workspace_bytes,
+                          int32_t tail, const void* gain, void* tail_out, float eps, void* hip_stream) {
+  if (!a || !w || m <= 0 || n <= 0 || k <= 0 || (k % 8) || (n % 8) || m > INT32_MAX || n > INT32_MAX ||
+      k > INT32_MAX || dtype != FP_DTYPE_BF16 || !workspace || workspace_bytes <= 0 ||
+      (reinterpret_cast<uintptr_t>(workspace) & 255) || !tail_out)
+    return fail(FP_ERR_INVALID, "fp_op_gemm_tail: bad size, alignment, dtype or null buffer");
+  const bool norm = tail == FP_TAIL_RMSNORM, swiglu = tail == FP_TAIL_SWIGLU;
+  if (!(norm && residual && gain && c) && !(swiglu && !residual))
+    return fail(FP_ERR_INVALID, "fp_op_gemm_tail: FP_TAIL_RMSNORM goes with residual = 1 (and gain, c), FP_TAIL_SWIGLU with residual = 0");
+  const int kind = norm ? fp::kTailRmsNorm : fp::kTailSwiGLU;
+  if (!fp::gemm_tail_fusable(dtype, m, n, k, (size_t)workspace_bytes, kind))
+    return fail(FP_ERR_INVALID, "fp_op_gemm_tail: this problem is not cut over K with %lld bytes of workspace "
+                                "(the tail rides on the split-K reduction); use the separate operators",
+                (long long)workspace_bytes);
+  const fp::GemmTail t{kind, gain, tail_out, eps};
+  fp::launch_gemm(dtype, a, w, c, m, n, k, residual, workspace, (size_t)workspace_bytes,
+                  reinterpret_cast<hipStream_t>(hip_stream), &t);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? FP_OK : fail(FP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(e));
 }
 
 int64_t fp_op_gemm_workspace_bytes(int32_t dtype, int64_t m, int64_t n, int64_t k) {

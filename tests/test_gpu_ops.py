@@ -166,6 +166,71 @@ def test_gemm_split_k_with_workspace(residual, m, n, k):
     assert torch.equal(again, out)
 
 
+@pytest.mark.parametrize("m,n,k", [(256, 4096, 4096), (1000, 4096, 14336), (130, 5120, 27648), (1, 4096, 4096), (513, 2056, 2048)])
+def test_split_k_reduction_fused_with_rmsnorm_equals_the_two_operators(m, n, k):
+    """Residual projection cut over K whose reduction kernel also normalises the updated row: the
+    residual and the normalised rows carry the bits of fp_op_gemm_ws followed by fp_op_rmsnorm,
+    and agree with the definition."""
+    B = _binding()
+    ws_bytes = B.fp_op_gemm_workspace_bytes(1, m, n, k)
+    assert ws_bytes > 0
+    a = I.normal_tensor((m, k), 1.0, 45, torch.bfloat16, "cuda")
+    w = I.normal_tensor((n, k), 0.02, 46, torch.bfloat16, "cuda")
+    gain = (1.0 + I.normal_tensor((n,), 0.1, 47, torch.float32, "cuda")).to(torch.bfloat16)
+    x0 = I.normal_tensor((m, n), 1.0, 48, torch.float32, "cuda")
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+    x_two, x_fused = x0.clone(), x0.clone()
+    h_two = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+    h_fused = torch.full((m + 2, n), 7.0, dtype=torch.bfloat16, device="cuda")
+    torch.cuda.synchronize()
+    B.fp_op_gemm_ws(1, a.data_ptr(), w.data_ptr(), x_two.data_ptr(), m, n, k, True, ws.data_ptr(), ws_bytes)
+    B.fp_op_rmsnorm(1, x_two.data_ptr(), gain.data_ptr(), h_two.data_ptr(), m, n, 1e-5)
+    B.fp_op_gemm_tail(a.data_ptr(), w.data_ptr(), x_fused.data_ptr(), m, n, k, True, ws.data_ptr(), ws_bytes,
+                      B.FP_TAIL_RMSNORM, gain.data_ptr(), h_fused[1:].data_ptr(), 1e-5)
+    torch.cuda.synchronize()
+    assert torch.equal(x_fused, x_two) and torch.equal(h_fused[1:m + 1], h_two)
+    assert torch.all(h_fused[0] == 7.0) and torch.all(h_fused[m + 1] == 7.0)
+    x_ref = x0.cpu().double() + O.linear(a.cpu(), w.cpu())
+    assert max_rel_err(x_fused, x_ref) <= TOL["bf16"]
+    assert max_rel_err(h_fused[1:m + 1], O.rmsnorm(x_ref, gain.cpu(), 1e-5)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("m,f,k", [(256, 14336, 4096), (100, 2048, 4096), (64, 13824, 5120)])
+def test_split_k_reduction_fused_with_swiglu_equals_the_two_operators(m, f, k):
+    """gate_up projection cut over K whose reduction kernel applies SiLU(gate)*up: the bits of
+    fp_op_gemm_ws into [M, 2F] followed by fp_op_silu_mul, without that intermediate."""
+    B = _binding()
+    ws_bytes = B.fp_op_gemm_workspace_bytes(1, m, 2 * f, k)
+    assert ws_bytes > 0
+    a = I.normal_tensor((m, k), 1.0, 49, torch.bfloat16, "cuda")
+    w = I.normal_tensor((2 * f, k), 0.02, 50, torch.bfloat16, "cuda")
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+    gu = torch.empty((m, 2 * f), dtype=torch.bfloat16, device="cuda")
+    two = torch.empty((m, f), dtype=torch.bfloat16, device="cuda")
+    fused = torch.full((m + 1, f), 7.0, dtype=torch.bfloat16, device="cuda")
+    torch.cuda.synchronize()
+    B.fp_op_gemm_ws(1, a.data_ptr(), w.data_ptr(), gu.data_ptr(), m, 2 * f, k, False, ws.data_ptr(), ws_bytes)
+    B.fp_op_silu_mul(1, gu.data_ptr(), two.data_ptr(), m, f)
+    B.fp_op_gemm_tail(a.data_ptr(), w.data_ptr(), 0, m, 2 * f, k, False, ws.data_ptr(), ws_bytes,
+                      B.FP_TAIL_SWIGLU, 0, fused.data_ptr())
+    torch.cuda.synchronize()
+    assert torch.equal(fused[:m], two) and torch.all(fused[m] == 7.0)
+    ref = O.silu_mul(O.linear(a.cpu(), w.cpu()))
+    assert max_rel_err(fused[:m], ref) <= TOL["bf16"]
+
+
+def test_fused_tail_is_refused_when_the_problem_is_not_cut():
+    B = _binding()
+    m, n, k = 4096, 4096, 4096                        # fills the chip with output tiles: no split-K, no tail
+    a = torch.zeros((m, k), dtype=torch.bfloat16, device="cuda")
+    x = torch.zeros((m, n), dtype=torch.float32, device="cuda")
+    ws = torch.empty((1 << 20,), dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.FlowPrefillError) as e:
+        B.fp_op_gemm_tail(a.data_ptr(), a.data_ptr(), x.data_ptr(), m, n, k, True, ws.data_ptr(), 1 << 20,
+                          B.FP_TAIL_RMSNORM, a.data_ptr(), a.data_ptr(), 1e-5)
+    assert e.value.status == B.FP_ERR_INVALID
+
+
 @pytest.mark.parametrize("name", ["bf16", "fp32"])
 @pytest.mark.parametrize("t,d", [(1, 256), (77, 4096), (5, 5120), (3, 8200), (2, 20000)])
 def test_rmsnorm_matches_definition(name, t, d):
