@@ -240,7 +240,7 @@ template <int READS, bool DMA>
 __device__ __forceinline__ void w4_block(f32x4_acc (&acc)[8][8], const W4Frags& cur, W4Frags& nxt,
                                          const bf16* rA, const bf16* rB, int pch,
                                          __amdgpu_buffer_rsrc_t rs_a, __amdgpu_buffer_rsrc_t rs_w, bf16* dA,
-                                         bf16* dB, const uint32_t (&voff)[8], int kbyte) {
+                                         bf16* dB, const uint32_t (&voff_a)[8], const uint32_t (&voff)[8], int kbyte) {
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
 #pragma unroll
@@ -255,7 +255,7 @@ __device__ __forceinline__ void w4_block(f32x4_acc (&acc)[8][8], const W4Frags& 
       }
       if (DMA && (j == 4 || j == 6)) {
         const int d = 2 * s + (j == 6);
-        if (d < 8) w4_dma(rs_a, dA + d * 8 * kBK, voff[d], kbyte);
+        if (d < 8) w4_dma(rs_a, dA + d * 8 * kBK, voff_a[d], kbyte);
         else w4_dma(rs_w, dB + (d - 8) * 8 * kBK, voff[d - 8], kbyte);
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -284,13 +284,17 @@ enum { kEpiBf16 = 0, kEpiResidual = 1, kEpiPartial = 2, kEpiSwiGLU = 3 };
 // row, rows (<= 256)}: the tile multiplies rows [first, first + rows) of A with expert's weight
 // matrix (W holds the experts' matrices back to back) into the same rows of C.  The grid is sized
 // for the worst case on the host; workgroups past groups[0] row tiles return at once.
+// With a_rows != null the rows of A are GATHERED: row r of the launch's row space is row a_rows[r]
+// of A (the tokens routed to an expert, fetched by the DMA from where they lie -- no gathered copy
+// of the activations is ever written); the kernel's M argument then holds the number of rows of A.
 template <int EPI, bool GROUPED = false>
 __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restrict__ A,
                                                            const bf16* __restrict__ W,
                                                            void* __restrict__ Cout, int M, int N,
                                                            int K, int tiles_m, int tiles_n,
                                                            int kt_per_split,
-                                                           const int32_t* __restrict__ groups) {
+                                                           const int32_t* __restrict__ groups,
+                                                           const int32_t* __restrict__ a_rows) {
   constexpr bool RESID = EPI == kEpiResidual;
   constexpr bool SWIGLU = EPI == kEpiSwiGLU;
   constexpr int BM = 256, BN = SWIGLU ? 128 : 256;   // output columns per tile
@@ -305,18 +309,30 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave & 1, wn = wave >> 1;           // 2 x 2 waves, wave tile 128 x 128 (SwiGLU: 128 x 64 outputs)
   int tile_m, tile_n, share_m;
+  int a_total_rows = 0;
   const int n_tiles = tiles_m * tiles_n;
   const int split = GROUPED ? 0 : blockIdx.x / n_tiles;   // which K range (0 unless split-K)
   if (GROUPED) {
-    const int ti = blockIdx.x / tiles_n;
-    if (ti >= groups[0]) return;                     // whole workgroup, before any barrier
+    // Consecutive workgroup ids go to the 8 XCDs in turn, each with its own L2.  Every XCD takes a
+    // contiguous run of the row-tile table (row tiles of one expert are neighbours in it) and walks
+    // it row tile by row tile, all column tiles of a row tile in a row: the workgroups an XCD has
+    // in flight then share the A panel of their row tile (all column tiles) and the W panels of
+    // their expert (its two or three row tiles) through that L2, instead of each fetching both
+    // panels from the fabric.
+    const int n_row_tiles = groups[0];
+    const int quota = (n_row_tiles + kXcds - 1) / kXcds;
+    const int in_xcd = blockIdx.x / kXcds;
+    const int ti = (blockIdx.x % kXcds) * quota + in_xcd / tiles_n;
+    if (in_xcd / tiles_n >= quota || ti >= n_row_tiles) return;   // whole workgroup, before any barrier
     const int expert = groups[1 + 3 * ti], first = groups[2 + 3 * ti];
+    a_total_rows = M;                                // gathered mode: the caller passes the rows of A here
     M = groups[3 + 3 * ti];
-    A += (int64_t)first * K;
+    if (a_rows) a_rows += first;                     // row r of the tile is row a_rows[r] of A
+    else A += (int64_t)first * K;
     W += (int64_t)expert * (SWIGLU ? 2 : 1) * N * K;
     Cout = reinterpret_cast<char*>(Cout) + (int64_t)first * N * (EPI == kEpiBf16 || SWIGLU ? 2 : 4);
     tile_m = 0;
-    tile_n = blockIdx.x - ti * tiles_n;
+    tile_n = in_xcd % tiles_n;
     share_m = ti;
   } else {
     tile_of_workgroup(blockIdx.x - split * n_tiles, tiles_m, tiles_n, tile_m, tile_n);
@@ -337,13 +353,30 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
     const int ch = (lane & 7) ^ ((row >> 1) & 7);
     voff[j] = (uint32_t)((row * K + ch * 8) * 2);
   }
+  // A rows of the same lanes: the same offsets, unless the rows are gathered (then absolute
+  // offsets into all of A, rows past the tile's end pointing outside the descriptor).
+  uint32_t voff_a[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) voff_a[j] = voff[j];
+  const bool gathered = GROUPED && a_rows != nullptr;
+  if (gathered) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int row = 64 * wave + j * 8 + (lane >> 3);          // tile_m = 0 in grouped launches
+      const int ch = (lane & 7) ^ ((row >> 1) & 7);
+      const int src = row < M ? a_rows[row] : -1;
+      voff_a[j] = src >= 0 ? (uint32_t)((src * K + ch * 8) * 2) : kOffOutOfRange;
+    }
+  }
   // Plain: W rows n0 + 64w ..; SwiGLU: LDS rows 128*wn + (0..63) are gate rows n0 + 64*wn + (0..63),
   // rows 128*wn + 64 + (0..63) the up rows N + the same -- waves 2*wn and 2*wn+1 fetch them.
   const int w_col0 = SWIGLU ? n0 + 64 * (wave >> 1) : n0 + 64 * wave;
   const int64_t w_row0 = SWIGLU ? (int64_t)(wave & 1) * N + w_col0 : w_col0;
-  const int a_rows = __builtin_amdgcn_readfirstlane(min(64, max(0, M - m0 - 64 * wave)));
+  const int a_panel_rows = __builtin_amdgcn_readfirstlane(min(64, max(0, M - m0 - 64 * wave)));
   const int w_rows = __builtin_amdgcn_readfirstlane(min(64, max(0, N - w_col0)));
-  const __amdgpu_buffer_rsrc_t rsrc_a = panel_rsrc(A + (int64_t)(m0 + 64 * wave) * K, (uint32_t)(a_rows * K * 2));
+  const __amdgpu_buffer_rsrc_t rsrc_a =
+      gathered ? panel_rsrc(A, (uint32_t)(a_total_rows * K * 2))
+               : panel_rsrc(A + (int64_t)(m0 + 64 * wave) * K, (uint32_t)(a_panel_rows * K * 2));
   const __amdgpu_buffer_rsrc_t rsrc_w = panel_rsrc(W + w_row0 * K, (uint32_t)(w_rows * K * 2));
   const __amdgpu_buffer_rsrc_t rsrc_none = panel_rsrc(A, 0u);
   bf16* const dA0 = sA0 + 64 * wave * kBK;
@@ -359,7 +392,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
   const int warm_rows_w = __builtin_amdgcn_readfirstlane(SWIGLU ? N + min(BN, N - n0) : min(BN, N - n0));
   const __amdgpu_buffer_rsrc_t rsrc_warm_a = panel_rsrc(A + (int64_t)m0 * K, (uint32_t)(warm_rows_a * K * 2));
   const __amdgpu_buffer_rsrc_t rsrc_warm_w = panel_rsrc(W + (int64_t)n0 * K, (uint32_t)(warm_rows_w * K * 2));
-  const __amdgpu_buffer_rsrc_t rsrc_warm = wave == 0 ? rsrc_warm_a : wave == 1 ? rsrc_warm_w : rsrc_none;
+  // (gathered rows are not contiguous: their lines are not warmed)
+  const __amdgpu_buffer_rsrc_t rsrc_warm = wave == 0 ? (gathered ? rsrc_none : rsrc_warm_a) : wave == 1 ? rsrc_warm_w : rsrc_none;
   const int warm_mask = wave == 0 ? 3 : 7;
   const int warm_id = wave == 0 ? (tile_n & 3) : (share_m & 7);
   uint32_t voff_warm;
@@ -386,13 +420,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
   // Prologue: k-tile 0 into stage 0 (awaited), k-tile 1 into stage 1 (in flight), then one warm-up
   // load, so that "all but one" is the right wait from the first barrier on.
 #pragma unroll
-  for (int s = 0; s < 8; ++s) w4_dma(rsrc_a, dA0 + s * 8 * kBK, voff[s], kbyte0);
+  for (int s = 0; s < 8; ++s) w4_dma(rsrc_a, dA0 + s * 8 * kBK, voff_a[s], kbyte0);
 #pragma unroll
   for (int s = 0; s < 8; ++s) w4_dma(rsrc_w, dB0 + s * 8 * kBK, voff[s], kbyte0);
   {
     const __amdgpu_buffer_rsrc_t ra1 = kt_count > 1 ? rsrc_a : rsrc_none, rw1 = kt_count > 1 ? rsrc_w : rsrc_none;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) w4_dma(ra1, dA1 + s * 8 * kBK, voff[s], kbyte0 + kBK * 2);
+    for (int s = 0; s < 8; ++s) w4_dma(ra1, dA1 + s * 8 * kBK, voff_a[s], kbyte0 + kBK * 2);
 #pragma unroll
     for (int s = 0; s < 8; ++s) w4_dma(rw1, dB1 + s * 8 * kBK, voff[s], kbyte0 + kBK * 2);
   }
@@ -429,12 +463,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
 #define W4_TILE(t, c, o)                                                                                      \
   {                                                                                                           \
     const int t2_ = (t) + 2;                                                                                  \
-    w4_block<4, false>(acc, f0, f1, rA##c, rB##c, pch1, rsrc_none, rsrc_none, dA##c, dB##c, voff, 0);         \
+    w4_block<4, false>(acc, f0, f1, rA##c, rB##c, pch1, rsrc_none, rsrc_none, dA##c, dB##c, voff_a, voff, 0); \
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);                                                                   \
     __builtin_amdgcn_s_waitcnt(kWaitVm1);                                                                     \
     w4_barrier();                                                                                             \
     w4_block<2, true>(acc, f1, f0, rA##o, rB##o, pch0, t2_ < kt_count ? rsrc_a : rsrc_none,                   \
-                      t2_ < kt_count ? rsrc_w : rsrc_none, dA##c, dB##c, voff, kbyte0 + t2_ * kBK * 2);       \
+                      t2_ < kt_count ? rsrc_w : rsrc_none, dA##c, dB##c, voff_a, voff, kbyte0 + t2_ * kBK * 2); \
     W4_WARM((t) + kWarmAhead);                                                                                \
     __builtin_amdgcn_sched_barrier(0);                                                                        \
   }
@@ -727,19 +761,21 @@ void launch_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t
   const int tiles_m = (int)((m + 255) / 256), tiles_n = (int)((f + 127) / 128);
   gemm_bf16_w4_kernel<kEpiSwiGLU><<<dim3((unsigned)(tiles_m * tiles_n)), 256, 0, s>>>(
       (const bf16*)a, (const bf16*)w_gate_up, out, (int)m, (int)f, (int)k, tiles_m, tiles_n,
-      (int)(k / kBK), nullptr);
+      (int)(k / kBK), nullptr, nullptr);
 }
 
 void launch_gemm_grouped(const void* a, const void* w, void* c, int64_t n, int64_t k, int swiglu,
-                         const int32_t* groups, int max_row_tiles, hipStream_t s) {
+                         const int32_t* groups, int max_row_tiles, const int32_t* a_rows, int64_t a_total_rows,
+                         hipStream_t s) {
   const int tiles_n = (int)(swiglu ? (n + 127) / 128 : (n + 255) / 256);
-  const dim3 grid((unsigned)(max_row_tiles * tiles_n));
+  const dim3 grid((unsigned)((max_row_tiles + kXcds - 1) / kXcds * kXcds * tiles_n));   // a whole number of row tiles per XCD
+  const int m_arg = a_rows ? (int)a_total_rows : 0;
   if (swiglu)
-    gemm_bf16_w4_kernel<kEpiSwiGLU, true><<<grid, 256, 0, s>>>((const bf16*)a, (const bf16*)w, c, 0, (int)n,
-                                                              (int)k, max_row_tiles, tiles_n, (int)(k / kBK), groups);
+    gemm_bf16_w4_kernel<kEpiSwiGLU, true><<<grid, 256, 0, s>>>((const bf16*)a, (const bf16*)w, c, m_arg, (int)n,
+                                                              (int)k, max_row_tiles, tiles_n, (int)(k / kBK), groups, a_rows);
   else
-    gemm_bf16_w4_kernel<kEpiBf16, true><<<grid, 256, 0, s>>>((const bf16*)a, (const bf16*)w, c, 0, (int)n,
-                                                            (int)k, max_row_tiles, tiles_n, (int)(k / kBK), groups);
+    gemm_bf16_w4_kernel<kEpiBf16, true><<<grid, 256, 0, s>>>((const bf16*)a, (const bf16*)w, c, m_arg, (int)n,
+                                                            (int)k, max_row_tiles, tiles_n, (int)(k / kBK), groups, a_rows);
 }
 
 size_t gemm_workspace_bytes(int dtype, int64_t m, int64_t n, int64_t k) {
@@ -756,13 +792,13 @@ static void launch_bf16_w4(const bf16* a, const bf16* w, void* c, int m, int n, 
   const int kt = k / kBK;
   if (splits <= 1) {
     gemm_bf16_w4_kernel<RESID ? kEpiResidual : kEpiBf16>
-        <<<dim3((unsigned)(tiles_m * tiles_n)), 256, 0, s>>>(a, w, c, m, n, k, tiles_m, tiles_n, kt, nullptr);
+        <<<dim3((unsigned)(tiles_m * tiles_n)), 256, 0, s>>>(a, w, c, m, n, k, tiles_m, tiles_n, kt, nullptr, nullptr);
     return;
   }
   const int per = (kt + splits - 1) / splits;
   const int used = (kt + per - 1) / per;             // every launched split has at least one k-tile
   gemm_bf16_w4_kernel<kEpiPartial><<<dim3((unsigned)(tiles_m * tiles_n * used)), 256, 0, s>>>(
-      a, w, workspace, m, n, k, tiles_m, tiles_n, per, nullptr);
+      a, w, workspace, m, n, k, tiles_m, tiles_n, per, nullptr, nullptr);
   const int64_t mn = (int64_t)m * n;
   if (RESID && tail.kind == kTailRmsNorm)
     splitk_reduce_norm_kernel<<<dim3((unsigned)m), 256, 0, s>>>(workspace, (float*)c, (const bf16*)tail.gain,

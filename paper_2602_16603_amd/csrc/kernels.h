@@ -75,11 +75,13 @@ void launch_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t
                         int64_t k, hipStream_t s);
 // Grouped bf16 GEMM for mixture-of-experts layers (K % 64 == 0, n % 8 == 0): `groups` (device) =
 // {row tiles, then {expert, first row, rows <= 256} per row tile}; row tile i multiplies those
-// rows of a [*, k] with expert's matrix of w ([experts][n][k], or [experts][2n][k] gate rows then
-// up rows when swiglu) into the same rows of c [*, n] (bf16; swiglu: silu(gate)*up).  The grid
-// covers max_row_tiles row tiles; the surplus exits.
+// rows with expert's matrix of w ([experts][n][k], or [experts][2n][k] gate rows then up rows when
+// swiglu) into the same rows of c [*, n] (bf16; swiglu: silu(gate)*up).  The rows are rows of a
+// [*, k] itself (a_rows == null) or, gathered, rows a_rows[first row + r] of a [a_total_rows, k]
+// (a_total_rows * k < 2^30).  The grid covers max_row_tiles row tiles; the surplus exits.
 void launch_gemm_grouped(const void* a, const void* w, void* c, int64_t n, int64_t k, int swiglu,
-                         const int32_t* groups, int max_row_tiles, hipStream_t s);
+                         const int32_t* groups, int max_row_tiles, const int32_t* a_rows,
+                         int64_t a_total_rows, hipStream_t s);
 
 // Gathers positions 0..len-1 of one sequence (block table row `table_dev`, device) of one layer
 // into contiguous k_out/v_out [len, Hkv, D].
@@ -97,9 +99,9 @@ int moe_route_blocks(int64_t n_tokens);
 void launch_moe_route(const float* logits, int32_t* ids, float* wts, int32_t* slot_of, int32_t* plan,
                       int32_t* block_counts, int32_t* groups, int64_t n_tokens, int n_experts, int top_k,
                       hipStream_t s);
-void launch_moe_gather(const void* h, void* hp, const int32_t* ids, const int32_t* plan,
-                       const int32_t* block_counts, int32_t* slot_of, int64_t n_tokens, int top_k,
-                       int n_experts, int d, hipStream_t s);
+void launch_moe_index(const int32_t* ids, const int32_t* plan, const int32_t* block_counts,
+                      int32_t* slot_of, int32_t* row_token, int64_t n_tokens, int top_k, int n_experts,
+                      hipStream_t s);
 void launch_moe_combine(float* x, const void* y, const int32_t* slot_of, const float* wts,
                         int64_t n_tokens, int top_k, int d, hipStream_t s);
 

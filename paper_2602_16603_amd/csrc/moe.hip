@@ -2,8 +2,8 @@
 // `gate` operator -- a gated router -- and the `experts` operator -- several expert FFNs).
 // Router: softmax over all experts of h W_r^T, the top_k most probable experts per token (ties:
 // lower index), probabilities renormalised over the selected ones.  The expert FFNs run as two
-// grouped GEMMs over the tokens gathered per expert (the second one's rows are then combined,
-// weighted, into the residual stream).  The arithmetic of a token never depends on where in an
+// grouped GEMMs over per-expert row ranges (the first gathers the routed tokens' activations by
+// index; the second one's rows are then combined, weighted, into the residual stream).  The arithmetic of a token never depends on where in an
 // expert's row range it lands, so the (atomic, run-to-run varying) slot order does not reach the
 // results.
 #include "common.h"
@@ -150,25 +150,22 @@ __global__ __launch_bounds__(256) void moe_plan_kernel(int32_t* __restrict__ pla
   }
 }
 
-// One wave per (token, choice): the pair's row = expert's offset + its route workgroup's first
-// row for that expert + its rank there; copy the token's activations into that row.
-__global__ __launch_bounds__(256) void moe_gather_kernel(const bf16* __restrict__ h,
-                                                         bf16* __restrict__ hp,
-                                                         const int32_t* __restrict__ ids,
-                                                         const int32_t* __restrict__ plan,
-                                                         const int32_t* __restrict__ block_counts,
-                                                         int32_t* __restrict__ slot_of, int n_pairs,
-                                                         int top_k, int n_experts, int d) {
-  const int lane = threadIdx.x & 63;
-  const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);
+// One thread per (token, choice): the pair's row = expert's offset + its route workgroup's first
+// row for that expert + its rank there; leaves the row in slot_of and the token in row_token[row]
+// (the index the grouped GEMM gathers the activations by -- they are never copied).
+__global__ __launch_bounds__(256) void moe_index_kernel(const int32_t* __restrict__ ids,
+                                                        const int32_t* __restrict__ plan,
+                                                        const int32_t* __restrict__ block_counts,
+                                                        int32_t* __restrict__ slot_of,
+                                                        int32_t* __restrict__ row_token, int n_pairs,
+                                                        int top_k, int n_experts) {
+  const int pair = blockIdx.x * 256 + threadIdx.x;
   if (pair >= n_pairs) return;
   const int token = pair / top_k;
   const int e = ids[pair];
   const int slot = plan[e] + block_counts[(int64_t)(token / kRouteTokensPerBlock) * n_experts + e] + slot_of[pair];
-  if (lane == 0) slot_of[pair] = slot;             // the wave has read its rank from this entry above
-  const u32x4* src = reinterpret_cast<const u32x4*>(h + (int64_t)token * d);
-  u32x4* dst = reinterpret_cast<u32x4*>(hp + (int64_t)slot * d);
-  for (int c = lane; c < d / 8; c += 64) dst[c] = src[c];
+  slot_of[pair] = slot;
+  row_token[slot] = token;
 }
 
 // x[t] += sum_j wts[t][j] * y[slot_of[t][j]], j ascending, fp32.
@@ -202,12 +199,12 @@ void launch_moe_route(const float* logits, int32_t* ids, float* wts, int32_t* sl
   moe_plan_kernel<<<1, 256, 0, s>>>(plan, block_counts, groups, n_experts, n_blocks);
 }
 
-void launch_moe_gather(const void* h, void* hp, const int32_t* ids, const int32_t* plan,
-                       const int32_t* block_counts, int32_t* slot_of, int64_t n_tokens, int top_k,
-                       int n_experts, int d, hipStream_t s) {
+void launch_moe_index(const int32_t* ids, const int32_t* plan, const int32_t* block_counts,
+                      int32_t* slot_of, int32_t* row_token, int64_t n_tokens, int top_k, int n_experts,
+                      hipStream_t s) {
   const int64_t pairs = n_tokens * top_k;
-  moe_gather_kernel<<<dim3((unsigned)((pairs + 3) / 4)), 256, 0, s>>>((const bf16*)h, (bf16*)hp, ids, plan, block_counts,
-                                                                      slot_of, (int)pairs, top_k, n_experts, d);
+  moe_index_kernel<<<dim3((unsigned)((pairs + 255) / 256)), 256, 0, s>>>(ids, plan, block_counts, slot_of, row_token,
+                                                                        (int)pairs, top_k, n_experts);
 }
 
 void launch_moe_combine(float* x, const void* y, const int32_t* slot_of, const float* wts,

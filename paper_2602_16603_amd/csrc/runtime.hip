@@ -101,7 +101,8 @@ struct fp_prefill : fp::OpBackend {
   // mixture-of-experts scratch (device; null for dense models)
   float* moe_logits = nullptr; float* moe_wts = nullptr;
   int32_t *moe_ids = nullptr, *moe_slot = nullptr, *moe_plan = nullptr, *moe_groups = nullptr, *moe_blocks = nullptr;
-  void *moe_hp = nullptr, *moe_act = nullptr, *moe_y = nullptr;
+  int32_t* moe_rows = nullptr;         // token of every row of the experts' row space (gather index)
+  void *moe_act = nullptr, *moe_y = nullptr;
   int32_t moe_max_row_tiles = 0;
   bool swiglu_fused = false;   // op 6 writes act directly (fused GEMM epilogue, or fused split-K reduction); op 7 then has no work and gu is not allocated
   bool swiglu_epilogue = false;   // ... by the GEMM epilogue (the problem fills the chip); else by the split-K reduction
@@ -154,11 +155,13 @@ fp_status launch_op(fp_prefill* t, int32_t index) {
         fp::launch_moe_route(t->moe_logits, ids, wts, t->moe_slot, t->moe_plan, t->moe_blocks, t->moe_groups, T, E, k, s);
         break;
       case 7:   // experts, first half: gather per expert, gate/up projection + SiLU*up
-        fp::launch_moe_gather(t->h, t->moe_hp, ids, t->moe_plan, t->moe_blocks, t->moe_slot, T, k, E, (int)d, s);
-        fp::launch_gemm_grouped(t->moe_hp, w.w_gate_up, t->moe_act, F, d, 1, t->moe_groups, t->moe_max_row_tiles, s);
+        fp::launch_moe_index(ids, t->moe_plan, t->moe_blocks, t->moe_slot, t->moe_rows, T, k, E, s);
+        fp::launch_gemm_grouped(t->h, w.w_gate_up, t->moe_act, F, d, 1, t->moe_groups, t->moe_max_row_tiles,
+                                t->moe_rows, T, s);
         break;
       case 8:   // experts, second half: down projection, weighted sum into the residual stream
-        fp::launch_gemm_grouped(t->moe_act, w.w_down, t->moe_y, d, F, 0, t->moe_groups, t->moe_max_row_tiles, s);
+        fp::launch_gemm_grouped(t->moe_act, w.w_down, t->moe_y, d, F, 0, t->moe_groups, t->moe_max_row_tiles,
+                                nullptr, 0, s);
         fp::launch_moe_combine(t->x, t->moe_y, t->moe_slot, wts, T, k, (int)d, s);
         break;
     }
@@ -518,6 +521,9 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
         return fail(FP_ERR_INVALID, "cached_lens needs caller-provided block_tables");
   if (block_tables && max_blocks <= 0) return fail(FP_ERR_INVALID, "max_blocks must be positive");
   const fp_shape& sh = m->shape;
+  if (sh.n_experts > 0 && (int64_t)T * sh.hidden >= (int64_t)1 << 30)
+    return fail(FP_ERR_INVALID, "mixture-of-experts task of %d tokens: tokens x hidden must stay below 2^30 "
+                                "(the experts' GEMM gathers activation rows through 32-bit offsets)", T);
 
   fp_prefill* t = new (std::nothrow) fp_prefill(sh.n_layers * FP_OPS_PER_LAYER, boundary_mask & FP_BOUNDARY_EVERY_OP);
   if (!t) return fail(FP_ERR_OOM, "host allocation failed");
@@ -619,7 +625,7 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
   const size_t o_ml = carve(moe ? Tn * E * 4 : 0), o_mw = carve(moe ? pairs * 4 * sh.n_layers : 0),
                o_mi = carve(moe ? pairs * 4 * sh.n_layers : 0), o_ms = carve(moe ? pairs * 4 : 0),
                o_mp = carve(moe ? E * 4 : 0), o_mb = carve(moe ? (size_t)fp::moe_route_blocks(T) * E * 4 : 0), o_mg = carve(moe ? (1 + 3 * (size_t)t->moe_max_row_tiles) * 4 : 0),
-               o_mh = carve(moe ? pairs * d * e : 0), o_ma = carve(moe ? pairs * F * e : 0),
+               o_mh = carve(moe ? pairs * 4 : 0), o_ma = carve(moe ? pairs * F * e : 0),
                o_my = carve(moe ? pairs * d * e : 0);
   const size_t o_sk = carve(sk_bytes);
   const size_t n_int = tok_seq.size() + tok_pos.size() + t->cu.size() + t->cached.size() +
@@ -639,7 +645,7 @@ fp_status fp_prefill_begin(fp_model* m, const void* hidden_in, const int32_t* cu
     t->moe_logits = reinterpret_cast<float*>(base + o_ml); t->moe_wts = reinterpret_cast<float*>(base + o_mw);
     t->moe_ids = reinterpret_cast<int32_t*>(base + o_mi); t->moe_slot = reinterpret_cast<int32_t*>(base + o_ms);
     t->moe_plan = reinterpret_cast<int32_t*>(base + o_mp); t->moe_blocks = reinterpret_cast<int32_t*>(base + o_mb); t->moe_groups = reinterpret_cast<int32_t*>(base + o_mg);
-    t->moe_hp = base + o_mh; t->moe_act = base + o_ma; t->moe_y = base + o_my;
+    t->moe_rows = reinterpret_cast<int32_t*>(base + o_mh); t->moe_act = base + o_ma; t->moe_y = base + o_my;
   }
 
   // Metadata goes through the workspace's pinned staging buffer, so the upload is asynchronous
