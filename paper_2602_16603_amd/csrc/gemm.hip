@@ -394,13 +394,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
   const __amdgpu_buffer_rsrc_t rsrc_warm_w = panel_rsrc(W + (int64_t)n0 * K, (uint32_t)(warm_rows_w * K * 2));
   // (gathered rows are not contiguous: their lines are not warmed)
   const __amdgpu_buffer_rsrc_t rsrc_warm = wave == 0 ? (gathered ? rsrc_none : rsrc_warm_a) : wave == 1 ? rsrc_warm_w : rsrc_none;
-  const int warm_mask = wave == 0 ? 3 : 7;
-  const int warm_id = wave == 0 ? (tile_n & 3) : (share_m & 7);
+  // Grouped launches: a W panel is shared by the two or three row tiles of its expert only, so
+  // there every workgroup takes a quarter of the W lines (all 64 lanes, every 4th row) instead of
+  // an eighth.
+  constexpr int kWShares = GROUPED ? 4 : 8;
+  const int warm_mask = wave == 0 ? 3 : kWShares - 1;
+  const int warm_id = wave == 0 ? (tile_n & 3) : (share_m & (kWShares - 1));
   uint32_t voff_warm;
   {
-    const int r0 = lane * 8;                         // wave 1: W-stage row of this lane's share 0
+    const int r0 = lane * kWShares;                  // wave 1: W-stage row of this lane's share 0
     const int64_t wrow = SWIGLU ? (int64_t)((r0 >> 6) & 1) * N + 64 * (r0 >> 7) + (r0 & 63) : r0;
-    voff_warm = wave == 0 ? (uint32_t)(lane * 4 * K * 2) : lane < 32 ? (uint32_t)(wrow * K * 2) : kOffOutOfRange;
+    voff_warm = wave == 0 ? (uint32_t)(lane * 4 * K * 2) : r0 < 256 ? (uint32_t)(wrow * K * 2) : kOffOutOfRange;
   }
 
   // MFMA fragment addresses: lane reads row (lane%16) of each 16-row block, k-chunk 4*ks + lane/16
