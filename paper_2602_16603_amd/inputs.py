@@ -64,6 +64,8 @@ CONFIGS: Dict[str, dict] = {
     "cfg3": dict(shape=LLAMA3_8B, seed=3, lengths=None),          # lengths from lognormal_lengths
     "cfg4": dict(shape=LLAMA3_8B, seed=4, lengths=[32768]),
     "cfg5": dict(shape=QWEN25_32B, seed=5, lengths=[65536, 32768, 16384, 8192]),
+    # One short request of the kind cfg4's arrivals are (128..1024 tokens), through the full stack.
+    "short": dict(shape=LLAMA3_8B, seed=9, lengths=[256]),
     # Mixture-of-experts widening (not one of the baseline configurations): four layers of the
     # 30B-A3B shape, one 8192-token prompt.
     "moe": dict(shape=QWEN3_30B_A3B.with_layers(4), seed=7, lengths=[8192]),
