@@ -430,7 +430,9 @@ def main() -> int:
     for o, name in enumerate(B.MOE_OP_NAMES if getattr(spec, "n_experts", 0) else B.OP_NAMES):
         avg = statistics.fmean(op_ms[o])
         per_op[name] = {"ms": round(avg, 4)}
-        if per_layer[o] > 0:
+        if avg <= 0:
+            per_op[name]["note"] = "launches nothing here: carried out by the neighbouring operator's kernel"
+        elif per_layer[o] > 0:
             per_op[name]["tflops"] = round(per_layer[o] / (avg * 1e-3) / 1e12, 1)
             per_op[name]["roof_frac"] = round(per_layer[o] / (avg * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS, 3)
         elif o in hbm_bytes:
