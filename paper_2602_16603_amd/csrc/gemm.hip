@@ -203,15 +203,17 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16* _
 // ------------------------------------------------------------------------------------------
 constexpr int kWaitVm0 = 0x0F70;   // s_waitcnt vmcnt(0)           (expcnt/lgkmcnt untouched)
 constexpr int kWaitVm1 = 0x0F71;   // s_waitcnt vmcnt(1)
+constexpr int kWaitVm13 = 0x0F7D;  // s_waitcnt vmcnt(13)
 constexpr int kWaitVm17 = 0x4F71;  // s_waitcnt vmcnt(17)
 constexpr int kWaitLgkm0 = 0xC07F; // s_waitcnt lgkmcnt(0)         (vmcnt/expcnt untouched)
 constexpr int kWarmAhead = 3;      // k-tiles between the L2 warm-up load and the DMA of the same lines
 constexpr uint32_t kOffOutOfRange = 0x80000000u;   // a byte offset no descriptor here covers
 
 typedef float f32x4_acc __attribute__((ext_vector_type(4)));
-struct W4Frags {     // MFMA operands of one k-step (32 of K): eight 16-row blocks of A and of W
+template <int NJ>
+struct W4Frags {     // MFMA operands of one k-step (32 of K): eight 16-row blocks of A and NJ of W
   bf16x8 a[8];
-  bf16x8 b[8];
+  bf16x8 b[NJ];
 };
 
 // Raw buffer descriptor over `bytes` bytes at `base` (stride 0, 32-bit offsets, reads past the
@@ -225,7 +227,9 @@ __device__ __forceinline__ void w4_dma(__amdgpu_buffer_rsrc_t r, bf16* lds_rows,
   __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)lds_rows, 16, voff, kbyte, 0, 0);
 }
 
-// One k-step: 64 MFMAs from `cur` (A block s against the eight W blocks, s = 0..7).  Every other
+// One k-step: 8 NJ MFMAs from `cur` (A block s against the NJ W blocks, s = 0..7; NJ = 8: the
+// 256-column tile described here, NJ = 4: the 128-column tile of short requests, with half the W
+// fragments and DMA instructions in the same slots).  Every other
 // instruction sits alone behind an MFMA: READS fragment reads of the next k-step per A block (2:
 // spread over the k-step; 4: all in its first half, for the k-step that ends at the barrier, so
 // that the wait in front of the barrier finds them done), in the order of their first use (all of
@@ -236,27 +240,27 @@ __device__ __forceinline__ void w4_dma(__amdgpu_buffer_rsrc_t r, bf16* lds_rows,
 // overflows the completely used accumulation registers (the 8-pass 32x32x16 is tied by itself).
 // No accumulator is touched twice within 64 MFMAs, and LDS results reach the operands through
 // the s_waitcnt the compiler places for the asm inputs, so no software-managed hazard arises.
-template <int READS, bool DMA>
-__device__ __forceinline__ void w4_block(f32x4_acc (&acc)[8][8], const W4Frags& cur, W4Frags& nxt,
+template <int READS, bool DMA, int NJ>
+__device__ __forceinline__ void w4_block(f32x4_acc (&acc)[8][NJ], const W4Frags<NJ>& cur, W4Frags<NJ>& nxt,
                                          const bf16* rA, const bf16* rB, int pch,
                                          __amdgpu_buffer_rsrc_t rs_a, __amdgpu_buffer_rsrc_t rs_w, bf16* dA,
                                          bf16* dB, const uint32_t (&voff_a)[8], const uint32_t (&voff)[8], int kbyte) {
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < NJ; ++j) {
       asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[s][j]) : "v"(cur.b[j]), "v"(cur.a[s]));
       if (j < READS) {
         const int r = s * READS + j;
-        if (r < 16) {
-          if (r < 8) nxt.b[r] = *reinterpret_cast<const bf16x8*>(rB + r * 16 * kBK + pch);
-          else nxt.a[r - 8] = *reinterpret_cast<const bf16x8*>(rA + (r - 8) * 16 * kBK + pch);
+        if (r < NJ + 8) {
+          if (r < NJ) nxt.b[r] = *reinterpret_cast<const bf16x8*>(rB + r * 16 * kBK + pch);
+          else nxt.a[r - NJ] = *reinterpret_cast<const bf16x8*>(rA + (r - NJ) * 16 * kBK + pch);
         }
       }
-      if (DMA && (j == 4 || j == 6)) {
-        const int d = 2 * s + (j == 6);
+      if (DMA && (j == NJ / 2 || j == NJ / 2 + NJ / 4)) {
+        const int d = 2 * s + (j != NJ / 2);
         if (d < 8) w4_dma(rs_a, dA + d * 8 * kBK, voff_a[d], kbyte);
-        else w4_dma(rs_w, dB + (d - 8) * 8 * kBK, voff[d - 8], kbyte);
+        else if (d - 8 < NJ) w4_dma(rs_w, dB + (d - 8) * 8 * kBK, voff[d - 8], kbyte);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -287,7 +291,14 @@ enum { kEpiBf16 = 0, kEpiResidual = 1, kEpiPartial = 2, kEpiSwiGLU = 3 };
 // With a_rows != null the rows of A are GATHERED: row r of the launch's row space is row a_rows[r]
 // of A (the tokens routed to an expert, fetched by the DMA from where they lie -- no gathered copy
 // of the activations is ever written); the kernel's M argument then holds the number of rows of A.
-template <int EPI, bool GROUPED = false>
+//
+// NJ = 4: the tile is half as wide (128 W rows per stage, wave tile 128 x 64).  A request of a few
+// hundred tokens has one or two row tiles: the narrow tile doubles the number of output tiles, so
+// the chip is occupied with half as many K ranges -- half the fp32 partial sums through memory,
+// and the fused gate_up projection of a 256-token request needs no K ranges at all (measured: a
+// 256-token request through the 8B-shaped stack 7.3 -> 6.5 ms; from three row tiles on the MFMAs
+// bound the launch and the wide tile's operand reuse wins).
+template <int EPI, bool GROUPED = false, int NJ = 8>
 __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restrict__ A,
                                                            const bf16* __restrict__ W,
                                                            void* __restrict__ Cout, int M, int N,
@@ -297,17 +308,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
                                                            const int32_t* __restrict__ a_rows) {
   constexpr bool RESID = EPI == kEpiResidual;
   constexpr bool SWIGLU = EPI == kEpiSwiGLU;
-  constexpr int BM = 256, BN = SWIGLU ? 128 : 256;   // output columns per tile
+  constexpr int WR = 32 * NJ;                        // W rows per stage (256 or 128)
+  constexpr int Q = WR / 4;                          // of which each wave fetches this many
+  constexpr int BM = 256, BN = SWIGLU ? WR / 2 : WR; // output columns per tile
   __shared__ __attribute__((aligned(1024))) bf16 sA0[BM * kBK];
   __shared__ __attribute__((aligned(1024))) bf16 sA1[BM * kBK];
-  __shared__ __attribute__((aligned(1024))) bf16 sB0[256 * kBK];
-  __shared__ __attribute__((aligned(1024))) bf16 sB1[256 * kBK];
+  __shared__ __attribute__((aligned(1024))) bf16 sB0[256 * kBK];   // (32 KB each also when WR = 128: the epilogue
+  __shared__ __attribute__((aligned(1024))) bf16 sB1[256 * kBK];   //  stages 32 KB per wave through them)
   __shared__ __attribute__((aligned(256))) uint32_t sWarm[4 * 64];   // landing pad of the L2 warm-up loads
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave & 1, wn = wave >> 1;           // 2 x 2 waves, wave tile 128 x 128 (SwiGLU: 128 x 64 outputs)
+  const int wm = wave & 1, wn = wave >> 1;           // 2 x 2 waves, wave tile 128 x WR/2 (SwiGLU: 128 x WR/4 outputs)
   int tile_m, tile_n, share_m;
   int a_total_rows = 0;
   const int n_tiles = tiles_m * tiles_n;
@@ -368,12 +381,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
       voff_a[j] = src >= 0 ? (uint32_t)((src * K + ch * 8) * 2) : kOffOutOfRange;
     }
   }
-  // Plain: W rows n0 + 64w ..; SwiGLU: LDS rows 128*wn + (0..63) are gate rows n0 + 64*wn + (0..63),
-  // rows 128*wn + 64 + (0..63) the up rows N + the same -- waves 2*wn and 2*wn+1 fetch them.
-  const int w_col0 = SWIGLU ? n0 + 64 * (wave >> 1) : n0 + 64 * wave;
+  // Plain: W rows n0 + Q w ..; SwiGLU: LDS rows 2Q wn + (0..Q-1) are gate rows n0 + Q wn + (0..Q-1),
+  // rows 2Q wn + Q + (0..Q-1) the up rows N + the same -- waves 2*wn and 2*wn+1 fetch them.
+  const int w_col0 = SWIGLU ? n0 + Q * (wave >> 1) : n0 + Q * wave;
   const int64_t w_row0 = SWIGLU ? (int64_t)(wave & 1) * N + w_col0 : w_col0;
   const int a_panel_rows = __builtin_amdgcn_readfirstlane(min(64, max(0, M - m0 - 64 * wave)));
-  const int w_rows = __builtin_amdgcn_readfirstlane(min(64, max(0, N - w_col0)));
+  const int w_rows = __builtin_amdgcn_readfirstlane(min(Q, max(0, N - w_col0)));
   const __amdgpu_buffer_rsrc_t rsrc_a =
       gathered ? panel_rsrc(A, (uint32_t)(a_total_rows * K * 2))
                : panel_rsrc(A + (int64_t)(m0 + 64 * wave) * K, (uint32_t)(a_panel_rows * K * 2));
@@ -381,12 +394,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
   const __amdgpu_buffer_rsrc_t rsrc_none = panel_rsrc(A, 0u);
   bf16* const dA0 = sA0 + 64 * wave * kBK;
   bf16* const dA1 = sA1 + 64 * wave * kBK;
-  bf16* const dB0 = sB0 + 64 * wave * kBK;
-  bf16* const dB1 = sB1 + 64 * wave * kBK;
+  bf16* const dB0 = sB0 + Q * wave * kBK;
+  bf16* const dB1 = sB1 + Q * wave * kBK;
 
   // L2 warm-up sources: wave 0 lane l -> A row 4l + share, wave 1 lane l < 32 -> W-stage row 8l +
-  // share (SwiGLU: stage row r is gate row n0 + 64*(r/128) + r%64, or the up row N + that, for
-  // r%128 >= 64).  The share is added through the scalar offset.
+  // share (SwiGLU: stage row r is gate row n0 + Q*(r/2Q) + r%Q, or the up row N + that, for
+  // r%2Q >= Q).  The share is added through the scalar offset.
   uint32_t* const warm = sWarm + 64 * wave;
   const int warm_rows_a = __builtin_amdgcn_readfirstlane(min(BM, M - m0));
   const int warm_rows_w = __builtin_amdgcn_readfirstlane(SWIGLU ? N + min(BN, N - n0) : min(BN, N - n0));
@@ -403,8 +416,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
   uint32_t voff_warm;
   {
     const int r0 = lane * kWShares;                  // wave 1: W-stage row of this lane's share 0
-    const int64_t wrow = SWIGLU ? (int64_t)((r0 >> 6) & 1) * N + 64 * (r0 >> 7) + (r0 & 63) : r0;
-    voff_warm = wave == 0 ? (uint32_t)(lane * 4 * K * 2) : r0 < 256 ? (uint32_t)(wrow * K * 2) : kOffOutOfRange;
+    const int64_t wrow = SWIGLU ? (int64_t)((r0 / Q) & 1) * N + Q * (r0 / (2 * Q)) + (r0 % Q) : r0;
+    voff_warm = wave == 0 ? (uint32_t)(lane * 4 * K * 2) : r0 < WR ? (uint32_t)(wrow * K * 2) : kOffOutOfRange;
   }
 
   // MFMA fragment addresses: lane reads row (lane%16) of each 16-row block, k-chunk 4*ks + lane/16
@@ -414,8 +427,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
   const int pch0 = ((0 + quad) ^ key) << 3, pch1 = ((4 + quad) ^ key) << 3;
   const bf16* const rA0 = sA0 + (wm * 128 + frag_row) * kBK;
   const bf16* const rA1 = sA1 + (wm * 128 + frag_row) * kBK;
-  const bf16* const rB0 = sB0 + (wn * 128 + frag_row) * kBK;
-  const bf16* const rB1 = sB1 + (wn * 128 + frag_row) * kBK;
+  const bf16* const rB0 = sB0 + (wn * (WR / 2) + frag_row) * kBK;
+  const bf16* const rB1 = sB1 + (wn * (WR / 2) + frag_row) * kBK;
 
 #define W4_WARM(u)                                                                                            \
   __builtin_amdgcn_raw_ptr_buffer_load_lds((u) < kt_count ? rsrc_warm : rsrc_none,                            \
@@ -426,35 +439,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
 #pragma unroll
   for (int s = 0; s < 8; ++s) w4_dma(rsrc_a, dA0 + s * 8 * kBK, voff_a[s], kbyte0);
 #pragma unroll
-  for (int s = 0; s < 8; ++s) w4_dma(rsrc_w, dB0 + s * 8 * kBK, voff[s], kbyte0);
+  for (int s = 0; s < NJ; ++s) w4_dma(rsrc_w, dB0 + s * 8 * kBK, voff[s], kbyte0);
   {
     const __amdgpu_buffer_rsrc_t ra1 = kt_count > 1 ? rsrc_a : rsrc_none, rw1 = kt_count > 1 ? rsrc_w : rsrc_none;
 #pragma unroll
     for (int s = 0; s < 8; ++s) w4_dma(ra1, dA1 + s * 8 * kBK, voff_a[s], kbyte0 + kBK * 2);
 #pragma unroll
-    for (int s = 0; s < 8; ++s) w4_dma(rw1, dB1 + s * 8 * kBK, voff[s], kbyte0 + kBK * 2);
+    for (int s = 0; s < NJ; ++s) w4_dma(rw1, dB1 + s * 8 * kBK, voff[s], kbyte0 + kBK * 2);
   }
   W4_WARM(kWarmAhead - 1);
   __builtin_amdgcn_sched_barrier(0);
   // Cleared while the first k-tile is on its way.
-  f32x4_acc acc[8][8];
+  f32x4_acc acc[8][NJ];
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) asm volatile("" : "+a"(acc[i][j]));   // materialise the zeros here, not at first use
+    for (int j = 0; j < NJ; ++j) asm volatile("" : "+a"(acc[i][j]));   // materialise the zeros here, not at first use
   __builtin_amdgcn_sched_barrier(0);
-  __builtin_amdgcn_s_waitcnt(kWaitVm17);
+  __builtin_amdgcn_s_waitcnt(NJ == 8 ? kWaitVm17 : kWaitVm13);   // all but k-tile 1 (8 + NJ) and the warm-up load
   w4_barrier();
-  W4Frags f0, f1;
+  W4Frags<NJ> f0, f1;
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
-    f0.b[s] = *reinterpret_cast<const bf16x8*>(rB0 + s * 16 * kBK + pch0);
+    if (s < NJ) f0.b[s] = *reinterpret_cast<const bf16x8*>(rB0 + s * 16 * kBK + pch0);
     f0.a[s] = *reinterpret_cast<const bf16x8*>(rA0 + s * 16 * kBK + pch0);
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -467,11 +480,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
 #define W4_TILE(t, c, o)                                                                                      \
   {                                                                                                           \
     const int t2_ = (t) + 2;                                                                                  \
-    w4_block<4, false>(acc, f0, f1, rA##c, rB##c, pch1, rsrc_none, rsrc_none, dA##c, dB##c, voff_a, voff, 0); \
+    w4_block<4, false, NJ>(acc, f0, f1, rA##c, rB##c, pch1, rsrc_none, rsrc_none, dA##c, dB##c, voff_a, voff, 0); \
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);                                                                   \
     __builtin_amdgcn_s_waitcnt(kWaitVm1);                                                                     \
     w4_barrier();                                                                                             \
-    w4_block<2, true>(acc, f1, f0, rA##o, rB##o, pch0, t2_ < kt_count ? rsrc_a : rsrc_none,                   \
+    w4_block<2, true, NJ>(acc, f1, f0, rA##o, rB##o, pch0, t2_ < kt_count ? rsrc_a : rsrc_none,                   \
                       t2_ < kt_count ? rsrc_w : rsrc_none, dA##c, dB##c, voff_a, voff, kbyte0 + t2_ * kBK * 2); \
     W4_WARM((t) + kWarmAhead);                                                                                \
     __builtin_amdgcn_sched_barrier(0);                                                                        \
@@ -515,61 +528,63 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
   bf16* region = wave == 0 ? sA0 : wave == 1 ? sA1 : wave == 2 ? sB0 : sB1;
   const int rows_valid = __builtin_amdgcn_readfirstlane(min(128, max(0, M - m0 - wm * 128)));
   if (SWIGLU) {
-    // Accumulators [i][0..3] are gate, [i][4..7] up of outputs n0 + 64*wn + (0..63): staged as
-    // [128 rows][8 chunks of 8 bf16], chunk c of row r at position c ^ ((r>>1)&7).
+    // Accumulators [i][0..NJ/2-1] are gate, [i][NJ/2..NJ-1] up of outputs n0 + (WR/4)*wn + (0..WR/4-1):
+    // staged as [128 rows][CH = NJ chunks of 8 bf16], chunk c of row r at position c ^ ((r>>1) & (CH-1)).
+    constexpr int CH = NJ;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = i * 16 + frag_row;
-      const int rkey = (row >> 1) & 7;
+      const int rkey = (row >> 1) & (CH - 1);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < NJ / 2; ++j) {
         bf16x4 v;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
           const float g = static_cast<float>(static_cast<bf16>(acc[i][j][b]));
-          const float u = static_cast<float>(static_cast<bf16>(acc[i][4 + j][b]));
+          const float u = static_cast<float>(static_cast<bf16>(acc[i][NJ / 2 + j][b]));
           v[b] = static_cast<bf16>(silu_mul_f32(g, u));
         }
-        *reinterpret_cast<bf16x4*>(region + row * 64 + (((2 * j + (quad >> 1)) ^ rkey) << 3) + 4 * (quad & 1)) = v;
+        *reinterpret_cast<bf16x4*>(region + row * (CH * 8) + (((2 * j + (quad >> 1)) ^ rkey) << 3) + 4 * (quad & 1)) = v;
       }
     }
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);     // own wave's LDS writes have landed; no other wave touches the region
     bf16* cb = reinterpret_cast<bf16*>(Cout) + (int64_t)(m0 + wm * 128) * N;
     const __amdgpu_buffer_rsrc_t rc = panel_rsrc(cb, (uint32_t)(rows_valid * N * 2));
-    const int col = n0 + wn * 64 + (lane & 7) * 8;
-    const uint32_t cbyte = col < N ? (uint32_t)(((lane >> 3) * N + col) * 2) : kOffOutOfRange;
+    const int col = n0 + wn * (CH * 8) + (lane % CH) * 8;
+    const uint32_t cbyte = col < N ? (uint32_t)(((lane / CH) * N + col) * 2) : kOffOutOfRange;
 #pragma unroll
-    for (int it = 0; it < 16; ++it) {
+    for (int it = 0; it < 2 * CH; ++it) {
       const int idx = lane + it * 64;
-      const int row = idx >> 3, ch = idx & 7;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(region + row * 64 + ((ch ^ ((row >> 1) & 7)) << 3));
-      __builtin_amdgcn_raw_buffer_store_b128(v, rc, cbyte, it * 8 * N * 2, 0);
+      const int row = idx / CH, ch = idx % CH;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(region + row * (CH * 8) + ((ch ^ ((row >> 1) & (CH - 1))) << 3));
+      __builtin_amdgcn_raw_buffer_store_b128(v, rc, cbyte, it * (64 / CH) * N * 2, 0);
     }
   } else if (EPI == kEpiBf16) {
-    // [128 rows][16 chunks of 8 bf16], chunk c of row r at position c ^ (r & 15).
+    // [128 rows][CH = 2 NJ chunks of 8 bf16], chunk c of row r at position c ^ (r & (CH-1)).
+    constexpr int CH = 2 * NJ;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = i * 16 + frag_row;
-      const int rkey = row & 15;
+      const int rkey = row & (CH - 1);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
+      for (int j = 0; j < NJ; ++j) {
         bf16x4 v;
 #pragma unroll
         for (int b = 0; b < 4; ++b) v[b] = static_cast<bf16>(acc[i][j][b]);
-        *reinterpret_cast<bf16x4*>(region + row * 128 + (((2 * j + (quad >> 1)) ^ rkey) << 3) + 4 * (quad & 1)) = v;
+        *reinterpret_cast<bf16x4*>(region + row * (CH * 8) + (((2 * j + (quad >> 1)) ^ rkey) << 3) + 4 * (quad & 1)) = v;
       }
     }
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
     bf16* cb = reinterpret_cast<bf16*>(Cout) + (int64_t)(m0 + wm * 128) * N;
     const __amdgpu_buffer_rsrc_t rc = panel_rsrc(cb, (uint32_t)(rows_valid * N * 2));
-    const int col = n0 + wn * 128 + (lane & 15) * 8;
-    const uint32_t cbyte = col < N ? (uint32_t)(((lane >> 4) * N + col) * 2) : kOffOutOfRange;
+    const int col = n0 + wn * (CH * 8) + (lane % CH) * 8;
+    const uint32_t cbyte = col < N ? (uint32_t)(((lane / CH) * N + col) * 2) : kOffOutOfRange;
 #pragma unroll
-    for (int it = 0; it < 32; ++it) {
+    for (int it = 0; it < 2 * CH; ++it) {
       const int idx = lane + it * 64;
-      const int row = idx >> 4, ch = idx & 15;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(region + row * 128 + ((ch ^ (row & 15)) << 3));
-      __builtin_amdgcn_raw_buffer_store_b128(v, rc, cbyte, it * 4 * N * 2, 0);
+      const int row = idx / CH, ch = idx % CH;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(region + row * (CH * 8) + ((ch ^ (row & (CH - 1))) << 3));
+      __builtin_amdgcn_raw_buffer_store_b128(v, rc, cbyte, it * (64 / CH) * N * 2, 0);
     }
   } else {
     // fp32 residual (read-modify-write) or split-K partial (plain store into this split's [M][N]
@@ -579,9 +594,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const bf16* __restric
     float* cf = reinterpret_cast<float*>(Cout) + (EPI == kEpiPartial ? (int64_t)split * M * N : 0) +
                 (int64_t)(m0 + wm * 128) * N;
     const __amdgpu_buffer_rsrc_t rc = panel_rsrc(cf, (uint32_t)(rows_valid * N * 4));
-    const int col0 = n0 + wn * 128 + (lane & 15) * 4;
+    const int col0 = n0 + wn * (WR / 2) + (lane & 15) * 4;
 #pragma unroll
-    for (int jp = 0; jp < 2; ++jp) {
+    for (int jp = 0; jp < NJ / 4; ++jp) {
       const int col = col0 + jp * 64;
       const uint32_t cbyte = col < N ? (uint32_t)(((lane >> 4) * N + col) * 4) : kOffOutOfRange;   // N % 8 == 0: quads all-in or all-out
       f32x4 x[16];
@@ -742,30 +757,52 @@ __global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(const float* __
   }
 }
 
-// How many K ranges to cut a problem into so that a launch has about one workgroup per CU:
-// only when the 256x256 tiles alone leave most of the chip idle, and never below 8 k-tiles
-// (512 columns) per range.  1 = no split.
-static int w4_splits(int64_t m, int64_t n, int64_t k) {
-  const int64_t tiles = ((m + 255) / 256) * ((n + 255) / 256);
-  if (tiles <= 0 || tiles >= 160) return 1;
-  int s = (int)std::min<int64_t>(16, 256 / tiles);
+// Tile width and number of K ranges for a problem.  Enough 256-column tiles to occupy the chip, or
+// more than two row tiles (then the MFMAs bound the launch and the wide tile's operand reuse
+// counts: measured at 768 tokens and up): the 256-column tile.  Otherwise the 128-column tile.
+// Either is cut over K only as far as it takes to reach about one workgroup per CU, and never
+// below 8 k-tiles (512 columns) per range.
+struct W4Shape {
+  int nj;       // W blocks per wave tile: 8 (256-column tile) or 4 (128-column tile)
+  int splits;   // 1 = no split
+};
+static W4Shape w4_shape(int64_t m, int64_t n, int64_t k) {
+  const int64_t tiles_m = (m + 255) / 256;
+  const int64_t wide = tiles_m * ((n + 255) / 256);
+  if (wide >= 160) return {8, 1};
+  const bool narrow = tiles_m <= 2;
+  const int64_t tiles = std::max<int64_t>(1, narrow ? tiles_m * ((n + 127) / 128) : wide);
+  int s = (int)std::max<int64_t>(1, std::min<int64_t>(16, 256 / tiles));
   while (s > 1 && (k / kBK) / s < 8) --s;
-  return s;
+  return {narrow ? 4 : 8, s};
+}
+
+// Tile of the fused gate_up projection: 128 FFN columns when that occupies the chip or the
+// request has more than two row tiles, else 64.
+static int swiglu_nj(int64_t m, int64_t f) {
+  const int64_t tiles_m = (m + 255) / 256;
+  return tiles_m <= 2 && tiles_m * ((f + 127) / 128) < 160 ? 4 : 8;
 }
 
 bool gemm_swiglu_fusable(int dtype, int64_t m, int64_t f, int64_t k) {
   if (dtype != 1 || k % kBK != 0 || f % 8 != 0 || m <= 0) return false;
   if ((f + 256) * k * 2 >= (int64_t)kOffOutOfRange) return false;   // the kernel's 32-bit offsets into the [gate | up] panel
-  const int64_t tiles = ((m + 255) / 256) * ((f + 127) / 128);
-  return tiles >= 96 && w4_splits(m, 2 * f, k) == 1;
+  const int cols = swiglu_nj(m, f) * 16;
+  return ((m + 255) / 256) * ((f + cols - 1) / cols) >= 96;
 }
 
 void launch_gemm_swiglu(const void* a, const void* w_gate_up, void* out, int64_t m, int64_t f,
                         int64_t k, hipStream_t s) {
-  const int tiles_m = (int)((m + 255) / 256), tiles_n = (int)((f + 127) / 128);
-  gemm_bf16_w4_kernel<kEpiSwiGLU><<<dim3((unsigned)(tiles_m * tiles_n)), 256, 0, s>>>(
-      (const bf16*)a, (const bf16*)w_gate_up, out, (int)m, (int)f, (int)k, tiles_m, tiles_n,
-      (int)(k / kBK), nullptr, nullptr);
+  const int nj = swiglu_nj(m, f);
+  const int tiles_m = (int)((m + 255) / 256), tiles_n = (int)((f + nj * 16 - 1) / (nj * 16));
+  const dim3 grid((unsigned)(tiles_m * tiles_n));
+  if (nj == 8)
+    gemm_bf16_w4_kernel<kEpiSwiGLU><<<grid, 256, 0, s>>>((const bf16*)a, (const bf16*)w_gate_up, out, (int)m, (int)f,
+                                                         (int)k, tiles_m, tiles_n, (int)(k / kBK), nullptr, nullptr);
+  else
+    gemm_bf16_w4_kernel<kEpiSwiGLU, false, 4><<<grid, 256, 0, s>>>((const bf16*)a, (const bf16*)w_gate_up, out, (int)m,
+                                                                   (int)f, (int)k, tiles_m, tiles_n, (int)(k / kBK),
+                                                                   nullptr, nullptr);
 }
 
 void launch_gemm_grouped(const void* a, const void* w, void* c, int64_t n, int64_t k, int swiglu,
@@ -784,24 +821,25 @@ void launch_gemm_grouped(const void* a, const void* w, void* c, int64_t n, int64
 
 size_t gemm_workspace_bytes(int dtype, int64_t m, int64_t n, int64_t k) {
   if (dtype != 1 || k % kBK != 0) return 0;
-  const int s = w4_splits(m, n, k);
+  const int s = w4_shape(m, n, k).splits;
   return s > 1 ? (size_t)s * m * n * sizeof(float) : 0;
 }
 
 // tail: what follows the split-K reduction in the same kernel (kTailNone: nothing).
-template <bool RESID>
+template <bool RESID, int NJ>
 static void launch_bf16_w4(const bf16* a, const bf16* w, void* c, int m, int n, int k, int splits,
                            float* workspace, const GemmTail& tail, hipStream_t s) {
-  const int tiles_m = (m + 255) / 256, tiles_n = (n + 255) / 256;
+  constexpr int BN = 32 * NJ;
+  const int tiles_m = (m + 255) / 256, tiles_n = (n + BN - 1) / BN;
   const int kt = k / kBK;
   if (splits <= 1) {
-    gemm_bf16_w4_kernel<RESID ? kEpiResidual : kEpiBf16>
+    gemm_bf16_w4_kernel<RESID ? kEpiResidual : kEpiBf16, false, NJ>
         <<<dim3((unsigned)(tiles_m * tiles_n)), 256, 0, s>>>(a, w, c, m, n, k, tiles_m, tiles_n, kt, nullptr, nullptr);
     return;
   }
   const int per = (kt + splits - 1) / splits;
   const int used = (kt + per - 1) / per;             // every launched split has at least one k-tile
-  gemm_bf16_w4_kernel<kEpiPartial><<<dim3((unsigned)(tiles_m * tiles_n * used)), 256, 0, s>>>(
+  gemm_bf16_w4_kernel<kEpiPartial, false, NJ><<<dim3((unsigned)(tiles_m * tiles_n * used)), 256, 0, s>>>(
       a, w, workspace, m, n, k, tiles_m, tiles_n, per, nullptr, nullptr);
   const int64_t mn = (int64_t)m * n;
   if (RESID && tail.kind == kTailRmsNorm)
@@ -880,19 +918,20 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
     }
 }
 
-// Number of K ranges launch_gemm cuts the problem into with that much workspace (1 = uncut; 0 = the
+// Tile and number of K ranges launch_gemm uses with that much workspace (splits 1 = uncut; 0 = the
 // problem does not run on the fast kernel at all).
-static int w4_plan(int dtype, int64_t m, int64_t n, int64_t k, size_t workspace_bytes) {
-  if (dtype != 1 || k % kBK != 0 || n % 8 != 0 || n > (1 << 21) || k > (1 << 21)) return 0;
+static W4Shape w4_plan(int dtype, int64_t m, int64_t n, int64_t k, size_t workspace_bytes) {
+  if (dtype != 1 || k % kBK != 0 || n % 8 != 0 || n > (1 << 21) || k > (1 << 21)) return {8, 0};
   // (the size limits keep the fast kernel's 32-bit buffer offsets below kOffOutOfRange)
-  const int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
-  int splits = w4_splits(m, n, k);
-  if (splits > 1 && (size_t)splits * m * n * sizeof(float) > workspace_bytes) splits = 1;
-  return big_tiles * splits >= 96 ? splits : 0;
+  W4Shape p = w4_shape(m, n, k);
+  if (p.splits > 1 && (size_t)p.splits * m * n * sizeof(float) > workspace_bytes) p.splits = 1;
+  const int64_t tiles = ((m + 255) / 256) * ((n + 32 * p.nj - 1) / (32 * p.nj));
+  if (tiles * p.splits < 96) p.splits = 0;
+  return p;
 }
 
 bool gemm_tail_fusable(int dtype, int64_t m, int64_t n, int64_t k, size_t workspace_bytes, int tail_kind) {
-  if (w4_plan(dtype, m, n, k, workspace_bytes) <= 1) return false;      // tails ride on the split-K reduction
+  if (w4_plan(dtype, m, n, k, workspace_bytes).splits <= 1) return false;   // tails ride on the split-K reduction
   if (tail_kind == kTailRmsNorm) return n <= kTailNormCols;
   if (tail_kind == kTailSwiGLU) return n % 16 == 0;
   return false;
@@ -917,12 +956,16 @@ void launch_gemm(int dtype, const void* a, const void* w, void* c, int64_t m, in
   // K a multiple of 64 and enough 256x256 tiles (or enough K to split) to occupy the chip: the
   // one-wave-per-SIMD DMA kernel, split over K when the caller's workspace allows.  Otherwise (tiny or
   // odd-K problems): the register-staged kernel on 128x128 tiles.
-  const int splits = w4_plan(dtype, m, n, k, workspace_bytes);
+  const W4Shape plan = w4_plan(dtype, m, n, k, workspace_bytes);
+  const int splits = plan.splits;
   const GemmTail none{};
   const GemmTail& tl = tail && gemm_tail_fusable(dtype, m, n, k, workspace_bytes, tail->kind) ? *tail : none;
-  if (splits >= 1) {
-    if (residual) launch_bf16_w4<true>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, tl, s);
-    else launch_bf16_w4<false>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, tl, s);
+  if (splits >= 1 && plan.nj == 8) {
+    if (residual) launch_bf16_w4<true, 8>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, tl, s);
+    else launch_bf16_w4<false, 8>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, tl, s);
+  } else if (splits >= 1) {
+    if (residual) launch_bf16_w4<true, 4>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, tl, s);
+    else launch_bf16_w4<false, 4>(pa, pw, c, (int)m, (int)n, (int)k, splits, (float*)workspace, tl, s);
   } else {
     if (residual) launch_bf16_cfg<128, 128, 2, 2, true>(pa, pw, c, (int)m, (int)n, (int)k, s);
     else launch_bf16_cfg<128, 128, 2, 2, false>(pa, pw, c, (int)m, (int)n, (int)k, s);

@@ -125,8 +125,8 @@ def test_gemm_seeded_random_shapes(m, n, k, residual):
 
 @pytest.mark.parametrize("residual", [False, True])
 @pytest.mark.parametrize("m,n,k", [
-    (256, 6144, 4096), (1, 4096, 4096), (130, 4096, 14336), (1000, 4096, 4096), (1024, 6144, 4096),
-    (513, 4104, 1024), (200, 28672, 4096), (64, 5120, 27648), (777, 2056, 2048),
+    (256, 6144, 4096), (1, 4096, 4096), (130, 4096, 14336), (1000, 4096, 4096), (512, 6144, 4096),
+    (513, 4104, 1024), (200, 14336, 4096), (64, 5120, 27648), (777, 2056, 2048),
 ])
 def test_gemm_split_k_with_workspace(residual, m, n, k):
     """Short requests (the 128-1024-token prompts of the trace) leave too few output tiles to fill
@@ -195,7 +195,7 @@ def test_split_k_reduction_fused_with_rmsnorm_equals_the_two_operators(m, n, k):
     assert max_rel_err(h_fused[1:m + 1], O.rmsnorm(x_ref, gain.cpu(), 1e-5)) <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("m,f,k", [(256, 14336, 4096), (100, 2048, 4096), (64, 13824, 5120)])
+@pytest.mark.parametrize("m,f,k", [(256, 7168, 4096), (100, 2048, 4096), (64, 6912, 5120)])
 def test_split_k_reduction_fused_with_swiglu_equals_the_two_operators(m, f, k):
     """gate_up projection cut over K whose reduction kernel applies SiLU(gate)*up: the bits of
     fp_op_gemm_ws into [M, 2F] followed by fp_op_silu_mul, without that intermediate."""
@@ -261,11 +261,13 @@ def test_silu_mul_matches_definition(name, t, f):
 
 
 @pytest.mark.parametrize("m,f,k", [(8192, 14336, 4096), (1000, 14336, 4096), (3000, 1000, 256), (700, 27648, 5120),
-                                   (2304, 1536, 64), (2305, 1544, 576)])
+                                   (2304, 1536, 64), (2305, 1544, 576),
+                                   (256, 14336, 4096), (130, 14336, 4096), (200, 6152, 1024), (500, 3080, 512)])
 def test_fused_gate_up_swiglu_equals_the_two_operators(m, f, k):
     """The gate_up GEMM with SiLU(gate)*up in its epilogue gives the bits of the GEMM followed by
     the stand-alone silu_mul (ragged M, an FFN width that is not a multiple of the 128-column
-    tile, both 8B and 32B shapes), and both agree with the definition."""
+    tile, both 8B and 32B shapes; the last four shapes run on the 64-column tile of short
+    requests), and both agree with the definition."""
     B = _binding()
     a = I.normal_tensor((m, k), 1.0, 40, torch.bfloat16, "cuda")
     w = I.normal_tensor((2 * f, k), 0.02, 41, torch.bfloat16, "cuda")
@@ -278,7 +280,7 @@ def test_fused_gate_up_swiglu_equals_the_two_operators(m, f, k):
     B.fp_op_gemm_swiglu(a.data_ptr(), w.data_ptr(), fused.data_ptr(), m, f, k)
     torch.cuda.synchronize()
     assert torch.equal(fused, two)
-    rows = torch.tensor(sorted({0, 1, 255, 256, m // 2, m - 1}))
+    rows = torch.tensor(sorted(r for r in {0, 1, 255, 256, m // 2, m - 1} if r < m))
     ref = O.silu_mul(O.linear(a[rows].cpu().double(), w.cpu().double()))
     assert max_rel_err(fused[rows], ref) <= TOL["bf16"]
 
