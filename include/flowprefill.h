@@ -155,9 +155,10 @@ fp_status fp_prefill_begin(fp_model* model, const void* hidden_in /*device*/,
 fp_status fp_prefill_advance(fp_prefill* task, int32_t max_ops, int32_t* ops_done /*host*/);
 
 /* How many operators may be enqueued on the stream beyond the one known complete.  With k >= 1
- * the host launches operator i only after operator i-k has completed, so a signal is honoured
- * within k operators.  Default 2 (no launch bubble; at most the running and one queued operator
- * finish before the acknowledgement).  k = 0 removes the bound (and the per-operator event): the
+ * the host launches an operator only once all but the last k-1 of the operators enqueued before
+ * it have completed (operators that launch nothing -- their work rides in a neighbour's kernel --
+ * take no place in that window), so a signal is honoured within k operators.  Default 2 (no
+ * launch bubble; at most the running and one queued operator finish before the acknowledgement).  k = 0 removes the bound (and the per-operator event): the
  * host enqueues as fast as it can and a signal is honoured only after everything enqueued so far
  * has run -- meant for short requests whose operators last tens of microseconds.                 */
 fp_status fp_prefill_set_launch_ahead(fp_prefill* task, int32_t k);

@@ -59,15 +59,16 @@ class TaskCore {
       state_ = TaskState::Running;
     }
     int32_t issued = 0;
+    int32_t marked = 0;       // operators of this call with device work; the j-th one's marker is slot j % kMarkRing
     int result = kTaskOk;
-    int slot_of[kMarkRing];   // marker that covers the i-th operator of this call (ring over i), -1 = none
     int32_t cur = cursor_.load(std::memory_order_relaxed);
     while (cur < total_ && issued < max_ops) {
-      // Bound how far the host runs ahead of the device: operator i is enqueued only once operator
-      // i - launch_ahead has completed.
-      if (launch_ahead_ > 0 && issued >= launch_ahead_) {
-        const int s = slot_of[(issued - launch_ahead_) % kMarkRing];
-        if (s >= 0 && be.wait_mark(s) != 0) { result = kTaskErrDevice; break; }
+      // Bound how far the host runs ahead of the device: at most launch_ahead operators with
+      // device work are enqueued and not known complete (an operator without device work takes
+      // no place in that window).  A slot is re-marked only after its previous marker was waited
+      // for: launch_ahead <= kMarkRing.
+      if (launch_ahead_ > 0 && marked >= launch_ahead_) {
+        if (be.wait_mark((marked - launch_ahead_) % kMarkRing) != 0) { result = kTaskErrDevice; break; }
       }
       // Preemption check at the boundary behind the previous operator.
       const bool boundary = cur == 0 || ((mask_ >> ((cur - 1) % per_layer_)) & 1u);
@@ -82,13 +83,11 @@ class TaskCore {
       if (be.launch(cur, &launched) != 0) { result = kTaskErrDevice; break; }
       // One marker per operator serves the launch-ahead bound (and the backend's timing); an
       // operator without device work places none and completes with its predecessor.
-      int slot = issued > 0 ? slot_of[(issued - 1) % kMarkRing] : -1;
       if (launched && (launch_ahead_ > 0 || be.wants_marks())) {
-        slot = issued % kMarkRing;
-        if (be.mark(slot) != 0) { result = kTaskErrDevice; break; }
+        if (be.mark(marked % kMarkRing) != 0) { result = kTaskErrDevice; break; }
+        ++marked;
       }
       be.op_issued(issued, launched);
-      slot_of[issued % kMarkRing] = slot;
       ++cur;
       cursor_.store(cur, std::memory_order_release);
       ++issued;

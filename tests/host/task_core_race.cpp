@@ -38,17 +38,20 @@ struct FakeDevice : fp::OpBackend {
   std::mt19937 rng;
   FakeDevice(int32_t n, int32_t ahead, uint32_t seed) : total(n), launch_ahead(ahead), runs(n, 0), end_of(n), rng(seed) {}
 
-  void begin_call() override { ++calls; first_of_call = last + 1; }
+  std::vector<Clock::time_point> work_ends;   // completion times of this call's operators with device work
+  void begin_call() override { ++calls; first_of_call = last + 1; work_ends.clear(); }
   int launch(int32_t index, bool* launched) override {
     CHECK(index == last + 1);                       // in order, none skipped, none repeated
     CHECK(index < total);
-    // Launch-ahead bound: operator index - launch_ahead (of this call) must be complete by now.
-    if (launch_ahead > 0 && index - launch_ahead >= first_of_call)
-      CHECK(end_of[index - launch_ahead] <= Clock::now());
     *launched = index % 9 != 7;                     // one operator per layer has no device work
     if (*launched) {
+      // Launch-ahead bound: of this call's operators with device work, all but the last
+      // launch_ahead must be complete by now.
+      if (launch_ahead > 0 && (int32_t)work_ends.size() >= launch_ahead)
+        CHECK(work_ends[work_ends.size() - launch_ahead] <= Clock::now());
       const auto start = std::max(Clock::now(), free_at);
       free_at = start + std::chrono::microseconds(20 + rng() % 200);
+      work_ends.push_back(free_at);
     }
     end_of[index] = free_at;
     runs[index]++;
