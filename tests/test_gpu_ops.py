@@ -82,6 +82,36 @@ def test_gemm_fast_path_trip_counts_and_ragged_edges(residual, m, n, k):
     assert torch.all(buf[m:] == 7.0)
 
 
+@pytest.mark.parametrize("residual", [False, True])
+@pytest.mark.parametrize("m,n,k", [
+    (512, 6144, 64), (300, 6152, 128), (257, 6152, 192), (512, 6152, 448), (257, 6152, 576), (130, 12296, 704),
+    (257, 6152, 1088), (1, 12296, 1600),
+])
+def test_gemm_narrow_tile_trip_counts_and_ragged_edges(residual, m, n, k):
+    """The 128-column tile that requests of up to two row tiles run on, uncut (no workspace), on
+    every path of its K loop (1, 2, 3, 7, 9, 11, 17 and 25 k-tiles), with a last row tile of one
+    row and a last column tile of eight columns; rows behind the output must stay untouched."""
+    B = _binding()
+    assert B.fp_op_gemm_workspace_bytes(1, m, n, k) == 0 or k >= 1024   # (short K: not cut even with a workspace)
+    print(f"gemm narrow tile residual={residual} m={m} n={n} k={k}", flush=True)
+    a = I.normal_tensor((m, k), 1.0, 24, torch.bfloat16, "cuda")
+    w = I.normal_tensor((n, k), 0.05, 25, torch.bfloat16, "cuda")
+    td = torch.float32 if residual else torch.bfloat16
+    guard = 300
+    buf = torch.full((m + guard, n), 7.0, dtype=td, device="cuda")
+    if residual:
+        buf[:m] = I.normal_tensor((m, n), 1.0, 26, torch.float32, "cuda")
+    x0 = buf[:m].clone()
+    torch.cuda.synchronize()
+    B.fp_op_gemm(1, a.data_ptr(), w.data_ptr(), buf.data_ptr(), m, n, k, residual)
+    torch.cuda.synchronize()
+    ref = O.linear(a.cpu(), w.cpu())
+    if residual:
+        ref = ref + x0.cpu().double()
+    assert max_rel_err(buf[:m], ref) <= TOL["bf16"]
+    assert torch.all(buf[m:] == 7.0)
+
+
 def _random_gemm_shapes(count, seed):
     import random
     rng = random.Random(seed)

@@ -136,8 +136,9 @@ def test_8b_head_shapes_small_twin_bf16():
 
 @pytest.mark.parametrize("lengths", [[128], [512, 40], [1024]])
 def test_short_requests_8b_shape_use_split_k(lengths):
-    """The 128..1024-token requests of the preemption workload: too few 256x256 output tiles to
-    fill the chip, so the projections are split over K and reduced in a fixed order."""
+    """The 128..1024-token requests of the preemption workload: too few output tiles to fill the
+    chip, so the projections run on the 128-column tile (up to 512 tokens), are split over K and
+    reduced in a fixed order by kernels that also carry the small operator that follows."""
     spec = I.LLAMA3_8B.with_layers(1)
     total = sum(lengths)
     model, weights = build(spec, 26, "bf16", total_tokens=total, max_position=1024)
