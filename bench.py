@@ -81,7 +81,16 @@ def cpu_baseline(spec, seed, lengths, sample_layers):
     dt = time.perf_counter() - t0
     scale = spec.n_layers / sample_layers
     model, phys, logical = host_cpu()
+    # The larger configurations at the FLOP rate this sample measured (not run: hours of CPU time).
+    cpu_flops = sum(op_flops(sub, lengths)) * sample_layers / dt
+    extrapolated = {}
+    for name in ("cfg3", "cfg4", "cfg5"):
+        c = I.CONFIGS[name]
+        lens = c["lengths"] if c["lengths"] is not None else I.lognormal_lengths(16, c["seed"])
+        extrapolated[name] = {"seconds": round(sum(op_flops(c["shape"], lens)) * c["shape"].n_layers / cpu_flops, 1),
+                              "label": "extrapolated from this sample's FLOP rate, not measured"}
     return {"value": total / (dt * scale), "unit": "tokens/s", "cores": torch.get_num_threads(),
+            "tflops": round(cpu_flops / 1e12, 4), "extrapolated": extrapolated,
             "kind": "oracle", "seconds": dt, "cpu_model": model, "physical_cores": phys, "logical_cpus": logical,
             "sample": f"all {total} tokens of the prompt through {sample_layers} of {spec.n_layers} layers "
                       f"(fp64 oracle, {torch.get_num_threads()} threads); layers cost the same, time scaled by "
